@@ -1,0 +1,167 @@
+/*
+ * allocmoe.h — C ABI of the budget-constrained MoE layer forward of Alloc-MoE
+ * for one AMD MI355X (gfx950).
+ *
+ * One call of allocmoe_moe_forward computes, for the T tokens of one MoE layer,
+ *   1. routing scores  s[t,:] = Softmax(x_t W_gate)            (Section 3.1, Eq. (1))
+ *   2. the candidate set: each token's Top-K_orig scores, sorted descending
+ *                                                              (Section 3.3, Eq. (6))
+ *   3. Alloc-T: keep every token's Top-K_base, then the globally largest
+ *      B - T*K_base of the remaining candidates of the whole batch
+ *                                  (Section 3.3, Eqs. (7)-(9) and the procedure after them)
+ *   4. an expert-sorted dispatch of the selected (token, expert) pairs
+ *   5. the SwiGLU expert networks over only the selected pairs, plus the
+ *      always-on shared expert of the workload                 (Section 3.1, "one
+ *      feed-forward execution" per activation)
+ *   6. y_t = sum_i w_{t,i} E_i(x_t), w = retained score or 0   (Section 3.1, Eq. (2))
+ * The per-layer budget B is an input: it is what Alloc-L's offline dynamic
+ * programme (Section 3.2, Eqs. (3)-(5)) hands to the layer, as T*K_l.
+ *
+ * Conventions for every entry point
+ *   - Pointers named in a comment as "device" are device (HBM) addresses owned
+ *     by the caller; the library allocates nothing, frees nothing and keeps no
+ *     pointer after a call returns.  Descriptor structs are host memory.
+ *   - All matrices are dense row-major.  X [T,d]; W_gate [d,E]; expert e:
+ *     W1[e], W3[e] are [d,I], W2[e] is [I,d], E_e(x) = (silu(x W1) * (x W3)) W2;
+ *     shared expert Ws1, Ws3 [d,I_shared], Ws2 [I_shared,d].
+ *   - Work is enqueued on the given stream (a hipStream_t passed as void*, NULL
+ *     = the null stream); no call synchronises with the host or copies to it.
+ *   - Arguments are validated on the host before anything is enqueued; on an
+ *     error nothing was launched and outputs are untouched.  Return value: an
+ *     allocmoe_status; the library never aborts or throws across this boundary.
+ *   - Same inputs give bit-identical outputs from run to run (no atomics on
+ *     floating-point data, fixed summation orders).
+ *   - Scores, routing weights and all accumulation are fp32 whatever `dtype`.
+ *   - Ties (equal scores) go to the lower expert id inside a token and to the
+ *     lower token, then lower rank, across the batch.  NaN scores are not
+ *     supported.
+ */
+#ifndef ALLOCMOE_H
+#define ALLOCMOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef void *allocmoe_stream; /* hipStream_t */
+
+typedef enum {
+    ALLOCMOE_OK = 0,
+    ALLOCMOE_EINVAL = -1,     /* null pointer, bad enum, K_base > K, K > E, ...         */
+    ALLOCMOE_EBUDGET = -2,    /* budget < T*K_base (Eq. (9) infeasible) or > T*K        */
+    ALLOCMOE_ESHAPE = -3,     /* a size outside what the kernels support (see desc)     */
+    ALLOCMOE_EWORKSPACE = -4, /* workspace / packed buffer too small or misaligned      */
+    ALLOCMOE_EHIP = -5        /* a HIP runtime call (kernel launch) reported an error   */
+} allocmoe_status;
+
+typedef enum { ALLOCMOE_F32 = 0, ALLOCMOE_BF16 = 1 } allocmoe_dtype;
+
+/* One layer call.  Supported sizes: 1 <= T, T*K < 2^31; 1 <= E <= 64;
+ * 1 <= K <= min(E,16); 0 <= K_base <= K; d, I >= 1.  With dtype BF16
+ * additionally d, I and I_shared must be multiples of 64. */
+typedef struct {
+    int32_t T, d, E, I;   /* tokens, hidden size H, routed experts N, expert width      */
+    int32_t K, K_base;    /* K_orig candidates per token; guaranteed minimum per token  */
+    int64_t budget;       /* B = T*K_l routed activations, T*K_base <= B <= T*K          */
+    int32_t I_shared;     /* 0 = no shared expert; else its (fused) intermediate width  */
+    int32_t shared_gate;  /* 0: y += Shared(x);  1: y += sigmoid(x . w_sg) * Shared(x)  */
+    int32_t dtype;        /* allocmoe_dtype of X, Y and every weight matrix             */
+    int32_t flags;        /* reserved, must be 0                                        */
+} allocmoe_layer_desc;
+
+/* Weights, all device pointers, read-only.  gate_bias (fp32 [E], added to the
+ * logits before the softmax) and the shared-expert fields may be NULL.
+ * `packed` is the buffer written by allocmoe_pack_weights; with dtype BF16 the
+ * expert networks read only `packed` (W1..Ws2 may then be NULL), with dtype F32
+ * they read the row-major matrices and `packed` is ignored. */
+typedef struct {
+    const void *Wg;         /* [d,E]                                  */
+    const float *gate_bias; /* [E] or NULL                            */
+    const void *W1, *W3;    /* [E,d,I]                                */
+    const void *W2;         /* [E,I,d]                                */
+    const void *Ws1, *Ws3;  /* [d,I_shared] or NULL                   */
+    const void *Ws2;        /* [I_shared,d] or NULL                   */
+    const void *w_sg;       /* [d] or NULL (needed iff shared_gate)   */
+    const void *packed;     /* allocmoe_packed_bytes() bytes or NULL  */
+} allocmoe_weights;
+
+/* Byte offsets, inside the workspace of allocmoe_moe_forward, of the
+ * intermediates it leaves behind (for inspection and tests).  Types and shapes:
+ * scores f32 [T,E]; topk_ids i32 [T,K]; topk_s f32 [T,K]; keep_count i32 [T];
+ * shared_gate f32 [T]; expert_offsets i32 [E+1]; row_token, row_rank i32 [B];
+ * inv_row i32 [T,K]; H dtype [B,I]; Hs dtype [T,I_shared]; O f32 [B,d];
+ * Os f32 [T,d]. */
+typedef struct {
+    size_t scores, topk_ids, topk_s, keep_count, shared_gate;
+    size_t expert_offsets, row_token, row_rank, inv_row;
+    size_t H, Hs, O, Os;
+    size_t scratch; /* selection/dispatch scratch and tile map */
+    size_t total;   /* == allocmoe_workspace_bytes                                      */
+} allocmoe_ws_layout;
+
+/* Size in bytes of the workspace allocmoe_moe_forward needs for this
+ * descriptor.  The workspace is device memory, 256-byte aligned, contents
+ * undefined on entry, reusable across calls on the same stream.
+ * allocmoe_dispatch uses only its first allocmoe_ws_layout.scores bytes (the
+ * scratch region, which starts the workspace); allocmoe_route and
+ * allocmoe_route_from_scores use none (ws may be NULL). */
+allocmoe_status allocmoe_workspace_bytes(const allocmoe_layer_desc *desc, size_t *bytes);
+allocmoe_status allocmoe_workspace_layout(const allocmoe_layer_desc *desc,
+                                          allocmoe_ws_layout *layout);
+
+/* One-time re-tiling of the static expert weights (bf16 only) into the
+ * fragment order the matrix-core kernels stream: same bytes, same values, a
+ * different order.  `canonical` holds the row-major device matrices (W1, W3,
+ * W2 and, if I_shared > 0, Ws1, Ws3, Ws2); `packed` is a device buffer of
+ * packed_bytes >= allocmoe_packed_bytes(), 256-byte aligned.  Not part of the
+ * per-batch path: call once per layer at load time. */
+allocmoe_status allocmoe_packed_bytes(const allocmoe_layer_desc *desc, size_t *bytes);
+allocmoe_status allocmoe_pack_weights(const allocmoe_layer_desc *desc,
+                                      const allocmoe_weights *canonical, void *packed,
+                                      size_t packed_bytes, allocmoe_stream stream);
+
+/* Steps 1-3.  X: device [T,d] of desc->dtype; reads w->Wg, w->gate_bias.
+ * Outputs (device): scores f32 [T,E] (may be NULL), topk_ids i32 [T,K] and
+ * topk_s f32 [T,K] (each token's K largest scores, descending, ties by lower
+ * expert id), keep_count i32 [T]: token t keeps ranks 0..keep_count[t]-1, with
+ * K_base <= keep_count[t] <= K and sum_t keep_count[t] == budget. */
+allocmoe_status allocmoe_route(const allocmoe_layer_desc *desc, const void *X,
+                               const allocmoe_weights *w, float *scores, int32_t *topk_ids,
+                               float *topk_s, int32_t *keep_count, void *ws, size_t ws_bytes,
+                               allocmoe_stream stream);
+
+/* Steps 2-3 from caller-supplied scores (device f32 [T,E], finite): the entry
+ * point whose integer outputs are bit-exact functions of its input.  Uses T, E,
+ * K, K_base, budget of the descriptor. */
+allocmoe_status allocmoe_route_from_scores(const allocmoe_layer_desc *desc, const float *scores,
+                                           int32_t *topk_ids, float *topk_s,
+                                           int32_t *keep_count, void *ws, size_t ws_bytes,
+                                           allocmoe_stream stream);
+
+/* Step 4.  From topk_ids [T,K] and keep_count [T] (device) build the rows of
+ * the selected pairs ordered by (expert ascending, token ascending):
+ * expert_offsets i32 [E+1] (rows of expert e are offsets[e]..offsets[e+1]),
+ * row_token / row_rank i32 [budget] (the pair behind each row), inv_row i32
+ * [T,K] (row of pair (t,j), -1 if not kept).  sum_t keep_count[t] must equal
+ * desc->budget (not checked: it lives on the device). */
+allocmoe_status allocmoe_dispatch(const allocmoe_layer_desc *desc, const int32_t *topk_ids,
+                                  const int32_t *keep_count, int32_t *expert_offsets,
+                                  int32_t *row_token, int32_t *row_rank, int32_t *inv_row,
+                                  void *ws, size_t ws_bytes, allocmoe_stream stream);
+
+/* Steps 1-6.  X device [T,d], Y device [T,d], both desc->dtype.  The
+ * intermediates stay in the workspace at the offsets of
+ * allocmoe_workspace_layout. */
+allocmoe_status allocmoe_moe_forward(const allocmoe_layer_desc *desc, const void *X,
+                                     const allocmoe_weights *w, void *Y, void *ws,
+                                     size_t ws_bytes, allocmoe_stream stream);
+
+const char *allocmoe_status_string(allocmoe_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ALLOCMOE_H */

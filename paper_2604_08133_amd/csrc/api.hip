@@ -1,0 +1,321 @@
+// C ABI of the library (include/allocmoe.h): argument validation on the host,
+// workspace carving, and the launch sequence of the layer.  Nothing here
+// allocates, synchronises or copies to the host.
+#include "../../include/allocmoe.h"
+
+#include "kernels.hpp"
+
+namespace {
+
+using namespace allocmoe;
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+inline size_t elem_size(int dtype) { return dtype == ALLOCMOE_F32 ? 4u : 2u; }
+
+struct Scratch {       // offsets inside the scratch region (which starts the workspace)
+    size_t words, prefix, tile_info, bytes;
+    int64_t max_tiles;
+};
+
+inline int64_t max_tiles_for(const allocmoe_layer_desc* d, int bm) {
+    return d->budget / bm + d->E;   // >= sum_e ceil(M_e / bm) for any split of B rows
+}
+
+Scratch scratch_of(const allocmoe_layer_desc* d) {
+    Scratch s;
+    const size_t nb = (static_cast<size_t>(d->T) + 63) / 64;
+    size_t off = 0;
+    s.words = off;
+    off = align_up(off + nb * 64 * sizeof(uint64_t));
+    s.prefix = off;
+    off = align_up(off + nb * 64 * sizeof(int32_t));
+    s.tile_info = off;
+    s.max_tiles = max_tiles_for(d, kTileRowsSmall);
+    off = align_up(off + tile_info_ints(s.max_tiles) * sizeof(int32_t));
+    s.bytes = off;
+    return s;
+}
+
+allocmoe_status check_desc(const allocmoe_layer_desc* d) {
+    if (d == nullptr) return ALLOCMOE_EINVAL;
+    if (d->dtype != ALLOCMOE_F32 && d->dtype != ALLOCMOE_BF16) return ALLOCMOE_EINVAL;
+    if (d->flags != 0) return ALLOCMOE_EINVAL;
+    if (d->T < 1 || d->d < 1 || d->E < 1 || d->I < 1 || d->K < 1) return ALLOCMOE_EINVAL;
+    if (d->K_base < 0 || d->K_base > d->K || d->K > d->E) return ALLOCMOE_EINVAL;
+    if (d->I_shared < 0 || (d->shared_gate != 0 && d->shared_gate != 1)) return ALLOCMOE_EINVAL;
+    if (d->shared_gate && d->I_shared == 0) return ALLOCMOE_EINVAL;
+    if (d->E > 64 || d->K > 16) return ALLOCMOE_ESHAPE;
+    if (static_cast<int64_t>(d->T) * d->K >= (1ll << 31)) return ALLOCMOE_ESHAPE;
+    if (d->dtype == ALLOCMOE_BF16 && (d->d % 64 || d->I % 64 || d->I_shared % 64))
+        return ALLOCMOE_ESHAPE;
+    if (d->budget < static_cast<int64_t>(d->T) * d->K_base ||
+        d->budget > static_cast<int64_t>(d->T) * d->K)
+        return ALLOCMOE_EBUDGET;
+    return ALLOCMOE_OK;
+}
+
+allocmoe_status layout_of(const allocmoe_layer_desc* d, allocmoe_ws_layout* L) {
+    const allocmoe_status st = check_desc(d);
+    if (st != ALLOCMOE_OK) return st;
+    const size_t T = d->T, E = d->E, K = d->K, B = static_cast<size_t>(d->budget);
+    const size_t es = elem_size(d->dtype);
+    size_t off = 0;
+    auto take = [&off](size_t bytes) {
+        const size_t at = off;
+        off = align_up(off + bytes);
+        return at;
+    };
+    L->scratch = take(scratch_of(d).bytes);
+    L->scores = take(T * E * 4);
+    L->topk_ids = take(T * K * 4);
+    L->topk_s = take(T * K * 4);
+    L->keep_count = take(T * 4);
+    L->shared_gate = take(T * 4);
+    L->expert_offsets = take((E + 1) * 4);
+    L->row_token = take(B * 4);
+    L->row_rank = take(B * 4);
+    L->inv_row = take(T * K * 4);
+    L->H = take(B * d->I * es);
+    L->Hs = take(T * d->I_shared * es);
+    L->O = take(B * d->d * 4);
+    L->Os = take(d->I_shared ? T * d->d * 4 : 0);
+    L->total = off;
+    return ALLOCMOE_OK;
+}
+
+struct PackedLayout {   // element offsets inside the packed buffer
+    size_t p13, p2, ps13, ps2, total_elems;
+};
+
+PackedLayout packed_of(const allocmoe_layer_desc* d) {
+    PackedLayout p;
+    const size_t E = d->E, dd = d->d, I = d->I, Is = d->I_shared;
+    p.p13 = 0;
+    p.p2 = p.p13 + E * 2 * dd * I;
+    p.ps13 = p.p2 + E * I * dd;
+    p.ps2 = p.ps13 + 2 * dd * Is;
+    p.total_elems = p.ps2 + Is * dd;
+    return p;
+}
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+inline allocmoe_status hip_status(hipError_t e) { return e == hipSuccess ? ALLOCMOE_OK : ALLOCMOE_EHIP; }
+
+template <typename T>
+inline T* at(void* base, size_t off) { return reinterpret_cast<T*>(static_cast<char*>(base) + off); }
+
+#define ALLOCMOE_TRY(expr)                                  \
+    do {                                                    \
+        const allocmoe_status st_ = hip_status(expr);       \
+        if (st_ != ALLOCMOE_OK) return st_;                 \
+    } while (0)
+
+}  // namespace
+
+extern "C" {
+
+const char* allocmoe_status_string(allocmoe_status status) {
+    switch (status) {
+        case ALLOCMOE_OK: return "ok";
+        case ALLOCMOE_EINVAL: return "invalid argument";
+        case ALLOCMOE_EBUDGET: return "budget outside [T*K_base, T*K]";
+        case ALLOCMOE_ESHAPE: return "unsupported size";
+        case ALLOCMOE_EWORKSPACE: return "workspace or packed buffer too small or misaligned";
+        case ALLOCMOE_EHIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+allocmoe_status allocmoe_workspace_layout(const allocmoe_layer_desc* desc,
+                                          allocmoe_ws_layout* layout) {
+    if (layout == nullptr) return ALLOCMOE_EINVAL;
+    return layout_of(desc, layout);
+}
+
+allocmoe_status allocmoe_workspace_bytes(const allocmoe_layer_desc* desc, size_t* bytes) {
+    if (bytes == nullptr) return ALLOCMOE_EINVAL;
+    allocmoe_ws_layout L;
+    const allocmoe_status st = layout_of(desc, &L);
+    if (st == ALLOCMOE_OK) *bytes = L.total;
+    return st;
+}
+
+allocmoe_status allocmoe_packed_bytes(const allocmoe_layer_desc* desc, size_t* bytes) {
+    if (bytes == nullptr) return ALLOCMOE_EINVAL;
+    const allocmoe_status st = check_desc(desc);
+    if (st != ALLOCMOE_OK) return st;
+    if (desc->dtype != ALLOCMOE_BF16) return ALLOCMOE_EINVAL;
+    *bytes = align_up(packed_of(desc).total_elems * 2);
+    return ALLOCMOE_OK;
+}
+
+allocmoe_status allocmoe_pack_weights(const allocmoe_layer_desc* desc,
+                                      const allocmoe_weights* w, void* packed,
+                                      size_t packed_bytes, allocmoe_stream stream_) {
+    const allocmoe_status st = check_desc(desc);
+    if (st != ALLOCMOE_OK) return st;
+    if (desc->dtype != ALLOCMOE_BF16 || w == nullptr || packed == nullptr) return ALLOCMOE_EINVAL;
+    if (!w->W1 || !w->W3 || !w->W2) return ALLOCMOE_EINVAL;
+    if (desc->I_shared && (!w->Ws1 || !w->Ws3 || !w->Ws2)) return ALLOCMOE_EINVAL;
+    const PackedLayout p = packed_of(desc);
+    if (packed_bytes < p.total_elems * 2 || !aligned(packed, kAlign)) return ALLOCMOE_EWORKSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    const int E = desc->E, d = desc->d, I = desc->I, Is = desc->I_shared;
+    uint16_t* out = static_cast<uint16_t*>(packed);
+    const size_t dd = d, II = I;
+    ALLOCMOE_TRY(launch_pack_b(w->W1, E, d, I, out + p.p13, 2 * dd * II, 2 * dd * 32, 0, stream));
+    ALLOCMOE_TRY(launch_pack_b(w->W3, E, d, I, out + p.p13, 2 * dd * II, 2 * dd * 32, dd * 32, stream));
+    ALLOCMOE_TRY(launch_pack_b(w->W2, E, I, d, out + p.p2, II * dd, II * 32, 0, stream));
+    if (Is) {
+        const size_t SS = Is;
+        ALLOCMOE_TRY(launch_pack_b(w->Ws1, 1, d, Is, out + p.ps13, 2 * dd * SS, 2 * dd * 32, 0, stream));
+        ALLOCMOE_TRY(launch_pack_b(w->Ws3, 1, d, Is, out + p.ps13, 2 * dd * SS, 2 * dd * 32, dd * 32, stream));
+        ALLOCMOE_TRY(launch_pack_b(w->Ws2, 1, Is, d, out + p.ps2, SS * dd, SS * 32, 0, stream));
+    }
+    return ALLOCMOE_OK;
+}
+
+allocmoe_status allocmoe_route(const allocmoe_layer_desc* desc, const void* X,
+                               const allocmoe_weights* w, float* scores, int32_t* topk_ids,
+                               float* topk_s, int32_t* keep_count, void* ws, size_t ws_bytes,
+                               allocmoe_stream stream_) {
+    const allocmoe_status st = check_desc(desc);
+    if (st != ALLOCMOE_OK) return st;
+    if (!X || !w || !w->Wg || !topk_ids || !topk_s || !keep_count) return ALLOCMOE_EINVAL;
+    (void)ws;
+    (void)ws_bytes;   // the selection runs out of LDS; no device scratch needed here
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    ALLOCMOE_TRY(launch_route(desc->dtype, X, w->Wg, w->gate_bias, nullptr, desc->T, desc->d,
+                              desc->E, desc->K, scores, topk_ids, topk_s, nullptr, stream));
+    ALLOCMOE_TRY(launch_select(topk_s, desc->T, desc->K, desc->K_base, desc->budget, keep_count,
+                               stream));
+    return ALLOCMOE_OK;
+}
+
+allocmoe_status allocmoe_route_from_scores(const allocmoe_layer_desc* desc, const float* scores,
+                                           int32_t* topk_ids, float* topk_s,
+                                           int32_t* keep_count, void* ws, size_t ws_bytes,
+                                           allocmoe_stream stream_) {
+    const allocmoe_status st = check_desc(desc);
+    if (st != ALLOCMOE_OK) return st;
+    if (!scores || !topk_ids || !topk_s || !keep_count) return ALLOCMOE_EINVAL;
+    (void)ws;
+    (void)ws_bytes;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    ALLOCMOE_TRY(launch_topk_from_scores(scores, desc->T, desc->E, desc->K, topk_ids, topk_s, stream));
+    ALLOCMOE_TRY(launch_select(topk_s, desc->T, desc->K, desc->K_base, desc->budget, keep_count,
+                               stream));
+    return ALLOCMOE_OK;
+}
+
+allocmoe_status allocmoe_dispatch(const allocmoe_layer_desc* desc, const int32_t* topk_ids,
+                                  const int32_t* keep_count, int32_t* expert_offsets,
+                                  int32_t* row_token, int32_t* row_rank, int32_t* inv_row,
+                                  void* ws, size_t ws_bytes, allocmoe_stream stream_) {
+    const allocmoe_status st = check_desc(desc);
+    if (st != ALLOCMOE_OK) return st;
+    if (!topk_ids || !keep_count || !expert_offsets || !inv_row) return ALLOCMOE_EINVAL;
+    if (desc->budget > 0 && (!row_token || !row_rank)) return ALLOCMOE_EINVAL;
+    const Scratch s = scratch_of(desc);
+    if (ws == nullptr || ws_bytes < s.bytes || !aligned(ws, kAlign)) return ALLOCMOE_EWORKSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    ALLOCMOE_TRY(launch_dispatch(topk_ids, keep_count, desc->T, desc->K, desc->E, desc->budget,
+                                 expert_offsets, row_token, row_rank, inv_row,
+                                 at<uint64_t>(ws, s.words), at<int32_t>(ws, s.prefix),
+                                 kTileRowsSmall, nullptr, stream));
+    return ALLOCMOE_OK;
+}
+
+allocmoe_status allocmoe_moe_forward(const allocmoe_layer_desc* desc, const void* X,
+                                     const allocmoe_weights* w, void* Y, void* ws,
+                                     size_t ws_bytes, allocmoe_stream stream_) {
+    allocmoe_ws_layout L;
+    const allocmoe_status st = layout_of(desc, &L);
+    if (st != ALLOCMOE_OK) return st;
+    if (!X || !Y || !w || !w->Wg) return ALLOCMOE_EINVAL;
+    const bool bf16 = desc->dtype == ALLOCMOE_BF16;
+    const int Is = desc->I_shared;
+    if (bf16) {
+        if (!w->packed || !aligned(w->packed, kAlign)) return ALLOCMOE_EINVAL;
+    } else {
+        if (!w->W1 || !w->W3 || !w->W2) return ALLOCMOE_EINVAL;
+        if (Is && (!w->Ws1 || !w->Ws3 || !w->Ws2)) return ALLOCMOE_EINVAL;
+    }
+    if (desc->shared_gate && !w->w_sg) return ALLOCMOE_EINVAL;
+    if (ws == nullptr || ws_bytes < L.total || !aligned(ws, kAlign)) return ALLOCMOE_EWORKSPACE;
+    if (!aligned(X, 16) || !aligned(Y, 16)) return ALLOCMOE_EINVAL;
+
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    const int T = desc->T, d = desc->d, E = desc->E, I = desc->I, K = desc->K;
+    const int64_t B = desc->budget;
+    const Scratch s = scratch_of(desc);
+    char* base = static_cast<char*>(ws);
+    char* scr = base + L.scratch;
+    float* scores = at<float>(base, L.scores);
+    int32_t* topk_ids = at<int32_t>(base, L.topk_ids);
+    float* topk_s = at<float>(base, L.topk_s);
+    int32_t* keep_count = at<int32_t>(base, L.keep_count);
+    float* sgate = desc->shared_gate ? at<float>(base, L.shared_gate) : nullptr;
+    int32_t* expert_offsets = at<int32_t>(base, L.expert_offsets);
+    int32_t* row_token = at<int32_t>(base, L.row_token);
+    int32_t* row_rank = at<int32_t>(base, L.row_rank);
+    int32_t* inv_row = at<int32_t>(base, L.inv_row);
+    int32_t* tile_info = at<int32_t>(scr, s.tile_info);
+    void* H = base + L.H;
+    void* Hs = base + L.Hs;
+    float* O = at<float>(base, L.O);
+    float* Os = Is ? at<float>(base, L.Os) : nullptr;
+
+    // steps 1-2: scores and sorted candidates
+    ALLOCMOE_TRY(launch_route(desc->dtype, X, w->Wg, w->gate_bias,
+                              desc->shared_gate ? w->w_sg : nullptr, T, d, E, K, scores, topk_ids,
+                              topk_s, sgate, stream));
+    // steps 3-4: Alloc-T selection, dispatch, tile map
+    ALLOCMOE_TRY(launch_plan(topk_s, topk_ids, T, K, desc->K_base, B, E, keep_count,
+                             expert_offsets, row_token, row_rank, inv_row,
+                             at<uint64_t>(scr, s.words), at<int32_t>(scr, s.prefix),
+                             kTileRowsSmall, tile_info, stream));
+    // step 5: expert networks over the selected rows, then the shared expert
+    if (bf16) {
+        const PackedLayout p = packed_of(desc);
+        const uint16_t* pk = static_cast<const uint16_t*>(w->packed);
+        const size_t dd = d, II = I, SS = Is;
+        if (B > 0) {
+            ALLOCMOE_TRY(launch_ffn_bf16_stream(true, X, d, row_token, pk + p.p13, 2 * dd * II, d,
+                                                I, tile_info, s.max_tiles, 0, H, I, stream));
+            ALLOCMOE_TRY(launch_ffn_bf16_stream(false, H, I, nullptr, pk + p.p2, II * dd, I, d,
+                                                tile_info, s.max_tiles, 0, O, d, stream));
+        }
+        if (Is) {
+            ALLOCMOE_TRY(launch_ffn_bf16_stream(true, X, d, nullptr, pk + p.ps13, 2 * dd * SS, d,
+                                                Is, nullptr, 0, T, Hs, Is, stream));
+            ALLOCMOE_TRY(launch_ffn_bf16_stream(false, Hs, Is, nullptr, pk + p.ps2, SS * dd, Is, d,
+                                                nullptr, 0, T, Os, d, stream));
+        }
+    } else {
+        const float* Xf = static_cast<const float*>(X);
+        if (B > 0) {
+            ALLOCMOE_TRY(launch_ffn_f32(true, Xf, d, row_token, static_cast<const float*>(w->W1),
+                                        static_cast<const float*>(w->W3), d, I, tile_info,
+                                        s.max_tiles, 0, static_cast<float*>(H), I, stream));
+            ALLOCMOE_TRY(launch_ffn_f32(false, static_cast<const float*>(H), I, nullptr,
+                                        static_cast<const float*>(w->W2), nullptr, I, d, tile_info,
+                                        s.max_tiles, 0, O, d, stream));
+        }
+        if (Is) {
+            ALLOCMOE_TRY(launch_ffn_f32(true, Xf, d, nullptr, static_cast<const float*>(w->Ws1),
+                                        static_cast<const float*>(w->Ws3), d, Is, nullptr, 0, T,
+                                        static_cast<float*>(Hs), Is, stream));
+            ALLOCMOE_TRY(launch_ffn_f32(false, static_cast<const float*>(Hs), Is, nullptr,
+                                        static_cast<const float*>(w->Ws2), nullptr, Is, d, nullptr,
+                                        0, T, Os, d, stream));
+        }
+    }
+    // step 6: Eq. (2)
+    ALLOCMOE_TRY(launch_combine(desc->dtype, O, Os, inv_row, topk_s, keep_count, sgate, T, d, K, Y,
+                                stream));
+    return ALLOCMOE_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,70 @@
+// Score-weighted combine (Section 3.1, Eq. (2)): y_t = sum_i w_{t,i} E_i(x_t)
+// over the kept pairs of token t, the weight being the retained routing score
+// (no renormalisation), plus the always-on shared expert's output times its
+// gate.  A gather: one workgroup per token walks the token's kept ranks in
+// order j = 0, 1, ... and adds s[t,j] * O[inv_row[t,j], :] in fp32, then the
+// shared term, then rounds once to the output type.
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace allocmoe {
+
+template <typename TOut>
+__global__ __launch_bounds__(256) void combine_kernel(
+    const float* __restrict__ O, const float* __restrict__ Os, const int32_t* __restrict__ inv_row,
+    const float* __restrict__ topk_s, const int32_t* __restrict__ keep_count,
+    const float* __restrict__ sgate, int T, int d, int K, TOut* __restrict__ Y) {
+    const int t = blockIdx.x;
+    if (t >= T) return;
+    const int kt = min(K, keep_count[t]);
+    const int32_t* rows = inv_row + static_cast<size_t>(t) * K;
+    const float* wts = topk_s + static_cast<size_t>(t) * K;
+    const float g = Os ? (sgate ? sgate[t] : 1.f) : 0.f;
+    if ((d & 3) == 0) {
+        for (int c = threadIdx.x * 4; c < d; c += blockDim.x * 4) {
+            float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int j = 0; j < kt; ++j) {
+                const float4 o =
+                    *reinterpret_cast<const float4*>(O + static_cast<size_t>(rows[j]) * d + c);
+                acc.x += wts[j] * o.x;
+                acc.y += wts[j] * o.y;
+                acc.z += wts[j] * o.z;
+                acc.w += wts[j] * o.w;
+            }
+            if (Os) {
+                const float4 o = *reinterpret_cast<const float4*>(Os + static_cast<size_t>(t) * d + c);
+                acc.x += g * o.x;
+                acc.y += g * o.y;
+                acc.z += g * o.z;
+                acc.w += g * o.w;
+            }
+            const size_t off = static_cast<size_t>(t) * d + c;
+            store_elem(Y, off, acc.x);
+            store_elem(Y, off + 1, acc.y);
+            store_elem(Y, off + 2, acc.z);
+            store_elem(Y, off + 3, acc.w);
+        }
+    } else {
+        for (int c = threadIdx.x; c < d; c += blockDim.x) {
+            float acc = 0.f;
+            for (int j = 0; j < kt; ++j) acc += wts[j] * O[static_cast<size_t>(rows[j]) * d + c];
+            if (Os) acc += g * Os[static_cast<size_t>(t) * d + c];
+            store_elem(Y, static_cast<size_t>(t) * d + c, acc);
+        }
+    }
+}
+
+hipError_t launch_combine(int out_dtype, const float* O, const float* Os, const int32_t* inv_row,
+                          const float* topk_s, const int32_t* keep_count, const float* sgate,
+                          int T, int d, int K, void* Y, hipStream_t stream) {
+    const dim3 grid(T), block(256);
+    if (out_dtype == 0)
+        hipLaunchKernelGGL(combine_kernel<float>, grid, block, 0, stream, O, Os, inv_row, topk_s,
+                           keep_count, sgate, T, d, K, static_cast<float*>(Y));
+    else
+        hipLaunchKernelGGL(combine_kernel<bf16_t>, grid, block, 0, stream, O, Os, inv_row, topk_s,
+                           keep_count, sgate, T, d, K, static_cast<bf16_t*>(Y));
+    return hipGetLastError();
+}
+
+}  // namespace allocmoe

@@ -1,0 +1,151 @@
+// bf16 expert networks on the matrix cores (Section 3.1: one feed-forward
+// execution per selected pair), fp32 accumulation, from weights re-tiled once
+// into MFMA fragment order (pack.hip):
+//   H = silu(A W1) * (A W3)   (SWIGLU, bf16 out)    or    O = A W2   (fp32 out).
+//
+// Weight-streaming kernel.  For token counts where an expert sees only a few
+// rows the layer is bound by reading each active expert's weights once from
+// HBM.  A workgroup owns one (row tile of <= 32 rows, block of 32 output
+// columns); its 4 waves split the contraction dimension, each streaming its
+// slice of the packed weight fragments straight from global memory into MFMA B
+// operands (1 KB contiguous per wave-load, every byte read once), with many
+// independent loads in flight.  The A operand (<= 32 activation rows, L2
+// resident) is gathered per lane.  Partial accumulators meet in LDS in a fixed
+// order, so results are bitwise reproducible.
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace allocmoe {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+constexpr int kStreamWaves = 4;
+constexpr int kStreamUnroll = 8;
+
+// 32x32 accumulator layout of v_mfma_f32_32x32x16_bf16: register r of lane l
+// holds C[8*(r/4) + 4*(l/32) + r%4][l%32].
+__device__ __forceinline__ int acc_row(int r, int l) { return 8 * (r / 4) + 4 * (l / 32) + (r % 4); }
+
+template <bool SWIGLU>
+__global__ __launch_bounds__(kStreamWaves* kWave) void ffn_bf16_stream_kernel(
+    const bf16_t* __restrict__ A, int lda, const int32_t* __restrict__ row_map,
+    const bf16_t* __restrict__ Bp, size_t group_stride, int Kd, int N,
+    const int32_t* __restrict__ tile_info, int M_dense, void* __restrict__ Cv, int ldc) {
+    constexpr int NACC = SWIGLU ? 2 : 1;
+    __shared__ float red[kStreamWaves][NACC][16][kWave];
+
+    const int n_blocks = N / 32;
+    const int tile = blockIdx.x / n_blocks, nb = blockIdx.x % n_blocks;
+    int e, row0, rows;
+    if (tile_info != nullptr) {
+        if (tile >= tile_info[0]) return;
+        const int32_t* ent = tile_info + 4 + 4 * static_cast<size_t>(tile);
+        e = ent[0];
+        row0 = ent[1];
+        rows = ent[2];
+    } else {
+        e = 0;
+        row0 = tile * 32;
+        if (row0 >= M_dense) return;
+        rows = min(32, M_dense - row0);
+    }
+    const int lane = lane_id(), wave = threadIdx.x / kWave;
+    const int KB = Kd / 16;                 // k16 steps in total
+    const int steps = KB / kStreamWaves;    // per wave (Kd is a multiple of 64)
+    const int kb0 = wave * steps;
+
+    // packed B: for this expert and column block, KB fragments of 64 x bf16x8
+    // (W1 stream, then for SWIGLU the W3 stream)
+    const bf16x8* b1 = reinterpret_cast<const bf16x8*>(
+                           Bp + static_cast<size_t>(e) * group_stride +
+                           static_cast<size_t>(nb) * (static_cast<size_t>(NACC) * Kd * 32)) +
+                       static_cast<size_t>(kb0) * kWave + lane;
+    const bf16x8* b3 = b1 + static_cast<size_t>(KB) * kWave;
+
+    // A: lane (m = l%32, kg = l/32) reads 8 consecutive k of its row per step
+    const int m = lane % 32, kg = lane / 32;
+    const bool a_ok = m < rows;
+    long src = 0;
+    if (a_ok) {
+        const int r = row0 + m;
+        src = row_map ? row_map[r] : r;
+    }
+    const bf16x8* ap =
+        reinterpret_cast<const bf16x8*>(A + static_cast<size_t>(src) * lda) + kb0 * 2 + kg;
+
+    f32x16 acc1 = {0}, acc3 = {0};
+    const bf16x8 zero = {0};
+    int s = 0;
+    for (; s + kStreamUnroll <= steps; s += kStreamUnroll) {
+        bf16x8 av[kStreamUnroll], w1[kStreamUnroll], w3[kStreamUnroll];
+#pragma unroll
+        for (int u = 0; u < kStreamUnroll; ++u) {
+            w1[u] = __builtin_nontemporal_load(b1 + static_cast<size_t>(s + u) * kWave);
+            if (SWIGLU) w3[u] = __builtin_nontemporal_load(b3 + static_cast<size_t>(s + u) * kWave);
+            av[u] = a_ok ? ap[(s + u) * 2] : zero;
+        }
+#pragma unroll
+        for (int u = 0; u < kStreamUnroll; ++u) {
+            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[u], w1[u], acc1, 0, 0, 0);
+            if (SWIGLU) acc3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[u], w3[u], acc3, 0, 0, 0);
+        }
+    }
+    for (; s < steps; ++s) {
+        const bf16x8 w1 = __builtin_nontemporal_load(b1 + static_cast<size_t>(s) * kWave);
+        const bf16x8 av = a_ok ? ap[s * 2] : zero;
+        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, w1, acc1, 0, 0, 0);
+        if (SWIGLU) {
+            const bf16x8 w3 = __builtin_nontemporal_load(b3 + static_cast<size_t>(s) * kWave);
+            acc3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, w3, acc3, 0, 0, 0);
+        }
+    }
+
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        red[wave][0][r][lane] = acc1[r];
+        if (SWIGLU) red[wave][NACC - 1][r][lane] = acc3[r];
+    }
+    __syncthreads();
+    // 16 x 64 accumulator slots, 256 threads: 4 slots each, waves summed in order
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int slot = threadIdx.x + 256 * q, r = slot / kWave, l = slot % kWave;
+        float v1 = 0.f, v3 = 0.f;
+#pragma unroll
+        for (int w = 0; w < kStreamWaves; ++w) {
+            v1 += red[w][0][r][l];
+            if (SWIGLU) v3 += red[w][NACC - 1][r][l];
+        }
+        const int mr = acc_row(r, l), n = nb * 32 + (l % 32);
+        if (mr < rows) {
+            const size_t off = static_cast<size_t>(row0 + mr) * ldc + n;
+            if (SWIGLU)
+                static_cast<bf16_t*>(Cv)[off] = f32_to_bf16((v1 / (1.f + __expf(-v1))) * v3);
+            else
+                static_cast<float*>(Cv)[off] = v1;
+        }
+    }
+}
+
+hipError_t launch_ffn_bf16_stream(bool swiglu, const void* A, int lda, const int32_t* row_map,
+                                  const void* Bp, size_t group_stride_elems, int Kd, int N,
+                                  const int32_t* tile_info, int64_t max_tiles, int M_dense,
+                                  void* C, int ldc, hipStream_t stream) {
+    const int64_t tiles = tile_info ? max_tiles : (M_dense + 31) / 32;
+    if (tiles <= 0) return hipSuccess;
+    const dim3 grid(static_cast<unsigned>(tiles * (N / 32))), block(kStreamWaves * kWave);
+    if (swiglu)
+        hipLaunchKernelGGL(ffn_bf16_stream_kernel<true>, grid, block, 0, stream,
+                           static_cast<const bf16_t*>(A), lda, row_map,
+                           static_cast<const bf16_t*>(Bp), group_stride_elems, Kd, N, tile_info,
+                           M_dense, C, ldc);
+    else
+        hipLaunchKernelGGL(ffn_bf16_stream_kernel<false>, grid, block, 0, stream,
+                           static_cast<const bf16_t*>(A), lda, row_map,
+                           static_cast<const bf16_t*>(Bp), group_stride_elems, Kd, N, tile_info,
+                           M_dense, C, ldc);
+    return hipGetLastError();
+}
+
+}  // namespace allocmoe

@@ -1,0 +1,61 @@
+// Host-side launchers of the gfx950 kernels (internal to the library; the
+// public boundary is include/allocmoe.h).  Every pointer is a device pointer.
+// Launchers only enqueue; they return hipGetLastError() of the launch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace allocmoe {
+
+// rows per tile of the grouped-GEMM tile map written by the plan kernel
+constexpr int kTileRowsSmall = 32;
+
+// tile_info layout: [0] = number of tiles; entry i at [4 + 4*i]: expert,
+// first row, rows in tile, 0.
+inline size_t tile_info_ints(int64_t max_tiles) { return 4 + 4 * static_cast<size_t>(max_tiles); }
+
+// ---- route.hip
+hipError_t launch_route(int dtype, const void* X, const void* Wg, const float* bias,
+                        const void* w_sg, int T, int d, int E, int K, float* scores,
+                        int32_t* topk_ids, float* topk_s, float* sgate, hipStream_t stream);
+hipError_t launch_topk_from_scores(const float* scores, int T, int E, int K, int32_t* topk_ids,
+                                   float* topk_s, hipStream_t stream);
+
+// ---- plan.hip
+hipError_t launch_select(const float* topk_s, int T, int K, int Kb, int64_t B,
+                         int32_t* keep_count, hipStream_t stream);
+hipError_t launch_dispatch(const int32_t* topk_ids, const int32_t* keep_count, int T, int K,
+                           int E, int64_t B, int32_t* expert_offsets, int32_t* row_token,
+                           int32_t* row_rank, int32_t* inv_row, uint64_t* words, int32_t* prefix,
+                           int bm, int32_t* tile_info, hipStream_t stream);
+hipError_t launch_plan(const float* topk_s, const int32_t* topk_ids, int T, int K, int Kb,
+                       int64_t B, int E, int32_t* keep_count, int32_t* expert_offsets,
+                       int32_t* row_token, int32_t* row_rank, int32_t* inv_row, uint64_t* words,
+                       int32_t* prefix, int bm, int32_t* tile_info, hipStream_t stream);
+
+// ---- ffn_f32.hip : C = A B (or silu(A B1) * (A B3)) over row tiles, fp32, row-major B
+// A rows are taken through row_map when it is not null.  With tile_info null the
+// rows 0..M_dense-1 form one group (group 0).  B1/B3: [G][Kd][N].
+hipError_t launch_ffn_f32(bool swiglu, const float* A, int lda, const int32_t* row_map,
+                          const float* B1, const float* B3, int Kd, int N,
+                          const int32_t* tile_info, int64_t max_tiles, int M_dense, float* C,
+                          int ldc, hipStream_t stream);
+
+// ---- ffn_bf16.hip : the same contraction on the matrix cores from packed weights
+hipError_t launch_ffn_bf16_stream(bool swiglu, const void* A, int lda, const int32_t* row_map,
+                                  const void* Bp, size_t group_stride_elems, int Kd, int N,
+                                  const int32_t* tile_info, int64_t max_tiles, int M_dense,
+                                  void* C, int ldc, hipStream_t stream);
+
+// ---- pack.hip : row-major [G][Kd][N] bf16 -> MFMA fragment order
+hipError_t launch_pack_b(const void* W, int G, int Kd, int N, void* out,
+                         size_t group_stride_elems, size_t nblock_stride_elems,
+                         size_t base_off_elems, hipStream_t stream);
+
+// ---- combine.hip : y_t = sum_j s[t,j] O[inv_row[t,j]] + g_t Os[t]
+hipError_t launch_combine(int out_dtype, const float* O, const float* Os, const int32_t* inv_row,
+                          const float* topk_s, const int32_t* keep_count, const float* sgate,
+                          int T, int d, int K, void* Y, hipStream_t stream);
+
+}  // namespace allocmoe

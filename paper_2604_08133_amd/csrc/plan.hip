@@ -1,0 +1,345 @@
+// Alloc-T selection and expert-sorted dispatch, as one single-workgroup "plan"
+// kernel (the data is a few hundred KB at most and lives in L2).
+//
+// Selection (Section 3.3, Eqs. (7)-(9) and the procedure after them): every
+// token keeps ranks j < K_base of its sorted candidate row; of the pool of the
+// remaining T*(K-K_base) candidates the B' = B - T*K_base largest are kept,
+// ties to the lower (token, rank).  Because rows are sorted, the kept ranks of
+// a token form a prefix, so the result is keep_count[t].
+//
+// The B'-th largest pool value is found exactly by narrowing a range [lo, hi]
+// of order-preserving u32 keys: each pass histograms the keys inside the range
+// into <= 2048 equal-width bins in LDS (integer counts: order of the atomic
+// increments cannot change the result), a block-wide suffix scan picks the bin
+// that holds the wanted rank, and the range shrinks to that bin until it holds
+// one key value v*.  Then a candidate is kept iff key > v*, or key == v* and
+// fewer than R equal keys precede it in (token, rank) order.
+//
+// Dispatch: rows of the kept pairs ordered by (expert, token), with no atomics:
+// for each batch of 64 tokens (lane = token) and each expert e the wave ballot
+// "token keeps e" is a 64-bit word M[e][batch]; the row of pair (t, e) is
+//   offset[e] + (kept pairs of e in earlier batches) + popcount(M[e][batch] below lane t).
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace allocmoe {
+
+constexpr int kPlanThreads = 1024;
+constexpr int kPlanWaves = kPlanThreads / kWave;
+constexpr int kBinsLog2 = 11;
+constexpr int kBins = 1 << kBinsLog2;
+
+struct PlanShared {
+    uint32_t hist[kBins];
+    uint32_t wave_tot[kPlanWaves];
+    uint32_t red_lo[kPlanWaves];
+    uint32_t red_hi[kPlanWaves];
+    uint32_t pick_bin;     // chosen bin of a pass
+    uint32_t pick_rank;    // wanted rank inside the chosen bin
+    uint32_t pick_count;   // number of keys inside the chosen bin
+    int32_t expert_total[kWave];
+    int32_t expert_off[kWave + 1];
+};
+
+// Exclusive block-wide prefix sum of one value per thread, in thread order.
+// Returns the exclusive prefix; *total (optional) receives the block sum.
+__device__ __forceinline__ uint32_t block_scan_excl(uint32_t v, uint32_t* wave_tot,
+                                                    uint32_t* total) {
+    const int lane = lane_id(), wave = threadIdx.x / kWave;
+    const uint32_t incl = static_cast<uint32_t>(wave_scan_incl(static_cast<int>(v)));
+    if (lane == kWave - 1) wave_tot[wave] = incl;
+    __syncthreads();
+    uint32_t base = 0, sum = 0;
+    for (int w = 0; w < kPlanWaves; ++w) {
+        const uint32_t x = wave_tot[w];
+        if (w < wave) base += x;
+        sum += x;
+    }
+    if (total) *total = sum;
+    __syncthreads();
+    return base + incl - v;
+}
+
+// keep_count[t] for all t.  topk_s: [T,K] rows sorted descending.
+__device__ void select_phase(PlanShared& sh, const float* topk_s, int T, int K, int Kb,
+                             int64_t B, int32_t* keep_count) {
+    const int tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
+    const int P = K - Kb;                       // pool entries per token
+    const int64_t n_pool = static_cast<int64_t>(T) * P;
+    const int64_t want = B - static_cast<int64_t>(T) * Kb;   // B'
+    if (want <= 0 || want >= n_pool) {          // nothing or everything from the pool
+        const int c = want <= 0 ? Kb : K;
+        for (int t = tid; t < T; t += kPlanThreads) keep_count[t] = c;
+        return;
+    }
+
+    if (tid == 0) {
+        sh.pick_bin = 0;
+        sh.pick_rank = 1;
+        sh.pick_count = 1;
+    }
+    // ---- pass 0: range of the pool keys
+    uint32_t lo = 0xFFFFFFFFu, hi = 0u;
+    for (int t = tid; t < T; t += kPlanThreads)
+        for (int j = Kb; j < K; ++j) {
+            const uint32_t k = ordered_key(topk_s[static_cast<size_t>(t) * K + j]);
+            lo = min(lo, k);
+            hi = max(hi, k);
+        }
+    lo = wave_min_u32(lo);
+    hi = wave_max_u32(hi);
+    if (lane == 0) {
+        sh.red_lo[wave] = lo;
+        sh.red_hi[wave] = hi;
+    }
+    __syncthreads();
+    lo = 0xFFFFFFFFu;
+    hi = 0u;
+    for (int w = 0; w < kPlanWaves; ++w) {
+        lo = min(lo, sh.red_lo[w]);
+        hi = max(hi, sh.red_hi[w]);
+    }
+    __syncthreads();
+
+    // ---- narrowing passes: rank `r` counts from the top of [lo, hi]
+    uint32_t r = static_cast<uint32_t>(want);
+    uint32_t in_range = static_cast<uint32_t>(n_pool);
+    while (lo < hi) {
+        const uint32_t width_m1 = hi - lo;                      // >= 1
+        const int bits = 32 - __builtin_clz(width_m1);          // width <= 2^bits
+        const int shift = bits > kBinsLog2 ? bits - kBinsLog2 : 0;
+        for (int b = tid; b < kBins; b += kPlanThreads) sh.hist[b] = 0;
+        __syncthreads();
+        for (int t = tid; t < T; t += kPlanThreads)
+            for (int j = Kb; j < K; ++j) {
+                const uint32_t k = ordered_key(topk_s[static_cast<size_t>(t) * K + j]);
+                if (k >= lo && k <= hi) atomicAdd(&sh.hist[(k - lo) >> shift], 1u);
+            }
+        __syncthreads();
+        // suffix sums over bins, two adjacent bins per thread, highest bins first:
+        // thread i owns bins kBins-1-2i (first) and kBins-2-2i (second)
+        const int b_first = kBins - 1 - 2 * tid, b_second = b_first - 1;
+        const uint32_t c_first = sh.hist[b_first], c_second = sh.hist[b_second];
+        const uint32_t above = block_scan_excl(c_first + c_second, sh.wave_tot, nullptr);
+        // `above` = number of in-range keys in bins higher than b_first
+        if (above < r && r <= above + c_first) {
+            sh.pick_bin = b_first;
+            sh.pick_rank = r - above;
+            sh.pick_count = c_first;
+        } else if (above + c_first < r && r <= above + c_first + c_second) {
+            sh.pick_bin = b_second;
+            sh.pick_rank = r - above - c_first;
+            sh.pick_count = c_second;
+        }
+        __syncthreads();
+        const uint32_t pb = sh.pick_bin;
+        r = sh.pick_rank;
+        in_range = sh.pick_count;
+        const uint32_t new_lo = lo + (pb << shift);
+        const uint32_t span_m1 = (shift == 0) ? 0u : ((1u << shift) - 1u);
+        const uint32_t new_hi = (hi - new_lo < span_m1) ? hi : new_lo + span_m1;
+        lo = new_lo;
+        hi = new_hi;
+        __syncthreads();
+    }
+    const uint32_t vstar = lo;      // key of the B'-th largest pool entry
+    const uint32_t n_equal = in_range;
+    const uint32_t R = r;           // how many of the keys == vstar are kept (1..n_equal)
+
+    if (R == n_equal) {             // no tie is split: a plain threshold
+        for (int t = tid; t < T; t += kPlanThreads) {
+            int c = Kb;
+            for (int j = Kb; j < K; ++j)
+                c += ordered_key(topk_s[static_cast<size_t>(t) * K + j]) >= vstar ? 1 : 0;
+            keep_count[t] = c;
+        }
+        return;
+    }
+    // ---- ties at the threshold: keep the first R equal keys in (token, rank)
+    // order.  Tokens are visited in rounds of 1024 (thread = token), so the
+    // order is (round, thread, rank); `seen` carries the equal keys of earlier
+    // rounds.
+    uint32_t seen = 0;
+    const int rounds = (T + kPlanThreads - 1) / kPlanThreads;
+    for (int it = 0; it < rounds; ++it) {
+        const int t = it * kPlanThreads + tid;
+        uint32_t gt = 0, eq = 0;
+        if (t < T)
+            for (int j = Kb; j < K; ++j) {
+                const uint32_t k = ordered_key(topk_s[static_cast<size_t>(t) * K + j]);
+                gt += k > vstar ? 1u : 0u;
+                eq += k == vstar ? 1u : 0u;
+            }
+        uint32_t round_total;
+        const uint32_t before = seen + block_scan_excl(eq, sh.wave_tot, &round_total);
+        seen += round_total;
+        if (t < T) {
+            // equal keys of one token sit at consecutive ranks right after its
+            // larger ones, so the first min(eq, R - before) of them are kept
+            const uint32_t room = before < R ? R - before : 0u;
+            keep_count[t] = Kb + static_cast<int>(gt + min(eq, room));
+        }
+    }
+}
+
+// Rows of the kept pairs in (expert, token) order.  words/prefix: scratch of
+// 64 * ceil(T/64) entries each (u64 / i32), indexed [batch * 64 + expert].
+__device__ void dispatch_phase(PlanShared& sh, const int32_t* topk_ids,
+                               const int32_t* keep_count, int T, int K, int E, int64_t max_rows,
+                               int32_t* expert_offsets, int32_t* row_token, int32_t* row_rank,
+                               int32_t* inv_row, uint64_t* words, int32_t* prefix) {
+    const int tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
+    const int n_batch = (T + kWave - 1) / kWave;
+
+    // ---- A: per batch, the 64-bit "who keeps expert e" words (lane e owns word e)
+    for (int b = wave; b < n_batch; b += kPlanWaves) {
+        const int t = b * kWave + lane;
+        uint64_t mine = 0;   // bit e: this token keeps expert e
+        if (t < T) {
+            const int kt = min(K, keep_count[t]);
+            for (int j = 0; j < kt; ++j)
+                mine |= 1ull << (topk_ids[static_cast<size_t>(t) * K + j] & (kWave - 1));
+        }
+        uint64_t col = 0;
+        for (int e = 0; e < E; ++e) {
+            const uint64_t w = __ballot((mine >> e) & 1ull);
+            if (lane == e) col = w;
+        }
+        words[static_cast<size_t>(b) * kWave + lane] = col;
+    }
+    __threadfence_block();
+    __syncthreads();
+
+    // ---- B: per expert, exclusive prefix over batches; then offsets over experts.
+    // thread (seg, e): 16 segments of batches per expert.
+    {
+        const int e = tid % kWave, seg = tid / kWave;
+        const int per_seg = (n_batch + kPlanWaves - 1) / kPlanWaves;
+        const int b0 = seg * per_seg, b1 = min(n_batch, b0 + per_seg);
+        int local = 0;
+        for (int b = b0; b < b1; ++b) local += __popcll(words[static_cast<size_t>(b) * kWave + e]);
+        sh.hist[seg * kWave + e] = static_cast<uint32_t>(local);
+        __syncthreads();
+        int base = 0, total = 0;
+        for (int s = 0; s < kPlanWaves; ++s) {
+            const int v = static_cast<int>(sh.hist[s * kWave + e]);
+            if (s < seg) base += v;
+            total += v;
+        }
+        int run = base;
+        for (int b = b0; b < b1; ++b) {
+            prefix[static_cast<size_t>(b) * kWave + e] = run;
+            run += __popcll(words[static_cast<size_t>(b) * kWave + e]);
+        }
+        if (seg == 0) {
+            // wave 0: lane e holds expert e's row count
+            const int incl = wave_scan_incl(e < E ? total : 0);
+            sh.expert_off[e + 1] = incl;
+            if (e == 0) sh.expert_off[0] = 0;
+        }
+        __threadfence_block();
+        __syncthreads();
+        if (tid <= E) expert_offsets[tid] = sh.expert_off[tid];
+    }
+
+    // ---- C: place every pair
+    for (int b = wave; b < n_batch; b += kPlanWaves) {
+        const int t = b * kWave + lane;
+        if (t >= T) continue;
+        const int kt = min(K, keep_count[t]);
+        const uint64_t below = lanemask_lt();
+        for (int j = 0; j < K; ++j) {
+            int row = -1;
+            if (j < kt) {
+                const int e = topk_ids[static_cast<size_t>(t) * K + j] & (kWave - 1);
+                const size_t idx = static_cast<size_t>(b) * kWave + e;
+                row = sh.expert_off[e] + prefix[idx] + __popcll(words[idx] & below);
+                if (row < max_rows) {   // holds whenever sum_t keep_count[t] <= budget
+                    row_token[row] = t;
+                    row_rank[row] = j;
+                }
+            }
+            inv_row[static_cast<size_t>(t) * K + j] = row;
+        }
+    }
+}
+
+// Tile map of the grouped GEMMs: one entry per (expert, block of `bm` rows).
+// tile_info[0] = number of tiles; entries (expert, first row, rows) follow.
+__device__ void tilemap_phase(PlanShared& sh, int E, int bm, int32_t* __restrict__ tile_info) {
+    const int tid = threadIdx.x;
+    if (tid < kWave) {
+        const int e = tid;
+        const int rows = e < E ? sh.expert_off[e + 1] - sh.expert_off[e] : 0;
+        const int nt = (rows + bm - 1) / bm;
+        const int incl = wave_scan_incl(nt);
+        const int first = incl - nt;
+        for (int i = 0; i < nt; ++i) {
+            int32_t* ent = tile_info + 4 + 4 * static_cast<size_t>(first + i);
+            ent[0] = e;
+            ent[1] = sh.expert_off[e] + i * bm;
+            ent[2] = min(bm, rows - i * bm);
+            ent[3] = 0;
+        }
+        if (e == kWave - 1) tile_info[0] = incl;
+    }
+}
+
+__global__ __launch_bounds__(kPlanThreads) void select_kernel(const float* topk_s, int T, int K,
+                                                              int Kb, int64_t B,
+                                                              int32_t* keep_count) {
+    __shared__ PlanShared sh;
+    select_phase(sh, topk_s, T, K, Kb, B, keep_count);
+}
+
+__global__ __launch_bounds__(kPlanThreads) void dispatch_kernel(
+    const int32_t* topk_ids, const int32_t* keep_count, int T, int K, int E, int64_t B,
+    int32_t* expert_offsets, int32_t* row_token, int32_t* row_rank, int32_t* inv_row,
+    uint64_t* words, int32_t* prefix, int bm, int32_t* tile_info) {
+    __shared__ PlanShared sh;
+    dispatch_phase(sh, topk_ids, keep_count, T, K, E, B, expert_offsets, row_token, row_rank,
+                   inv_row, words, prefix);
+    if (tile_info != nullptr) tilemap_phase(sh, E, bm, tile_info);
+}
+
+__global__ __launch_bounds__(kPlanThreads) void plan_kernel(
+    const float* topk_s, const int32_t* topk_ids, int T, int K, int Kb, int64_t B, int E,
+    int32_t* keep_count, int32_t* expert_offsets, int32_t* row_token, int32_t* row_rank,
+    int32_t* inv_row, uint64_t* words, int32_t* prefix, int bm, int32_t* tile_info) {
+    __shared__ PlanShared sh;
+    select_phase(sh, topk_s, T, K, Kb, B, keep_count);
+    __threadfence_block();
+    __syncthreads();
+    dispatch_phase(sh, topk_ids, keep_count, T, K, E, B, expert_offsets, row_token, row_rank,
+                   inv_row, words, prefix);
+    if (tile_info != nullptr) tilemap_phase(sh, E, bm, tile_info);
+}
+
+hipError_t launch_select(const float* topk_s, int T, int K, int Kb, int64_t B,
+                         int32_t* keep_count, hipStream_t stream) {
+    hipLaunchKernelGGL(select_kernel, dim3(1), dim3(kPlanThreads), 0, stream, topk_s, T, K, Kb, B,
+                       keep_count);
+    return hipGetLastError();
+}
+
+hipError_t launch_dispatch(const int32_t* topk_ids, const int32_t* keep_count, int T, int K,
+                           int E, int64_t B, int32_t* expert_offsets, int32_t* row_token,
+                           int32_t* row_rank, int32_t* inv_row, uint64_t* words, int32_t* prefix,
+                           int bm, int32_t* tile_info, hipStream_t stream) {
+    hipLaunchKernelGGL(dispatch_kernel, dim3(1), dim3(kPlanThreads), 0, stream, topk_ids,
+                       keep_count, T, K, E, B, expert_offsets, row_token, row_rank, inv_row,
+                       words, prefix, bm, tile_info);
+    return hipGetLastError();
+}
+
+hipError_t launch_plan(const float* topk_s, const int32_t* topk_ids, int T, int K, int Kb,
+                       int64_t B, int E, int32_t* keep_count, int32_t* expert_offsets,
+                       int32_t* row_token, int32_t* row_rank, int32_t* inv_row, uint64_t* words,
+                       int32_t* prefix, int bm, int32_t* tile_info, hipStream_t stream) {
+    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, stream, topk_s, topk_ids, T,
+                       K, Kb, B, E, keep_count, expert_offsets, row_token, row_rank, inv_row,
+                       words, prefix, bm, tile_info);
+    return hipGetLastError();
+}
+
+}  // namespace allocmoe

@@ -1,0 +1,171 @@
+// Routing scores and per-token candidates (Section 3.1, Eq. (1); Section 3.3,
+// Eq. (6)): logits = x W_gate (+bias), softmax over all E experts, then each
+// token's K largest scores in descending order (ties: lower expert id).
+//
+// Layout: one lane per expert (E <= 64).  A workgroup of 4 waves owns kTok
+// tokens; the waves split the hidden dimension, each lane accumulating the
+// logit of its expert, and the partial sums meet in LDS in a fixed order.
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace allocmoe {
+
+constexpr int kRouteTok = 4;    // tokens per workgroup
+constexpr int kRouteWaves = 4;  // waves per workgroup, splitting d
+
+// Wave-wide descending Top-K of one value per lane (lanes >= E hold nothing).
+// Lane j < K returns the j-th winner's lane (expert id) and value.
+__device__ __forceinline__ void wave_topk(float score, bool valid, int K, int& out_id,
+                                          float& out_s) {
+    const int lane = lane_id();
+    // larger score first; equal scores: lower lane first
+    uint64_t key = valid ? ((static_cast<uint64_t>(ordered_key(score)) << 32) |
+                            static_cast<uint32_t>(kWave - lane))
+                         : 0ull;
+    out_id = 0;
+    out_s = 0.f;
+    for (int j = 0; j < K; ++j) {
+        uint64_t best = wave_max_u64(key);
+        int win = kWave - static_cast<int>(best & 0xFFFFFFFFull);
+        float ws = __shfl(score, win, kWave);
+        if (lane == j) {
+            out_id = win;
+            out_s = ws;
+        }
+        if (lane == win) key = 0ull;
+    }
+}
+
+template <typename TIn>
+__global__ __launch_bounds__(kRouteWaves* kWave) void route_kernel(
+    const TIn* __restrict__ X, const TIn* __restrict__ Wg, const float* __restrict__ bias,
+    const TIn* __restrict__ w_sg, int T, int d, int E, int K, float* __restrict__ scores,
+    int32_t* __restrict__ topk_ids, float* __restrict__ topk_s, float* __restrict__ sgate) {
+    __shared__ float part[kRouteWaves][kRouteTok][kWave];
+    __shared__ float gpart[kRouteWaves][kRouteTok];
+
+    const int lane = lane_id();
+    const int wave = threadIdx.x / kWave;
+    const int t0 = blockIdx.x * kRouteTok;
+
+    // this wave's slice of the hidden dimension, in chunks of 64
+    const int chunks = (d + kWave - 1) / kWave;
+    const int per_wave = (chunks + kRouteWaves - 1) / kRouteWaves;
+    const int c_begin = wave * per_wave;
+    const int c_end = min(chunks, c_begin + per_wave);
+
+    float acc[kRouteTok];
+    float gacc[kRouteTok];
+#pragma unroll
+    for (int q = 0; q < kRouteTok; ++q) acc[q] = gacc[q] = 0.f;
+
+    const bool lane_is_expert = lane < E;
+    for (int c = c_begin; c < c_end; ++c) {
+        const int h0 = c * kWave;
+        const int h = h0 + lane;
+        float xv[kRouteTok];
+#pragma unroll
+        for (int q = 0; q < kRouteTok; ++q) {
+            const int t = t0 + q;
+            xv[q] = (t < T && h < d) ? load_f32(X, static_cast<size_t>(t) * d + h) : 0.f;
+        }
+        if (w_sg != nullptr) {
+            const float g = h < d ? load_f32(w_sg, h) : 0.f;
+#pragma unroll
+            for (int q = 0; q < kRouteTok; ++q) gacc[q] += xv[q] * g;
+        }
+        const int n = min(kWave, d - h0);
+#pragma unroll 8
+        for (int i = 0; i < n; ++i) {
+            const float wv =
+                lane_is_expert ? load_f32(Wg, static_cast<size_t>(h0 + i) * E + lane) : 0.f;
+#pragma unroll
+            for (int q = 0; q < kRouteTok; ++q) acc[q] += __shfl(xv[q], i, kWave) * wv;
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < kRouteTok; ++q) {
+        part[wave][q][lane] = acc[q];
+        if (w_sg != nullptr) {
+            const float g = wave_sum(gacc[q]);
+            if (lane == 0) gpart[wave][q] = g;
+        }
+    }
+    __syncthreads();
+
+    // wave q finishes token t0 + q
+    for (int q = wave; q < kRouteTok; q += kRouteWaves) {
+        const int t = t0 + q;
+        if (t >= T) continue;
+        float logit = 0.f;
+#pragma unroll
+        for (int w = 0; w < kRouteWaves; ++w) logit += part[w][q][lane];
+        if (bias != nullptr && lane_is_expert) logit += bias[lane];
+        if (!lane_is_expert) logit = -INFINITY;
+        const float m = wave_max(logit);
+        const float p = lane_is_expert ? expf(logit - m) : 0.f;
+        const float den = wave_sum(p);
+        const float s = p / den;
+        if (scores != nullptr && lane_is_expert) scores[static_cast<size_t>(t) * E + lane] = s;
+        int id;
+        float sv;
+        wave_topk(s, lane_is_expert, K, id, sv);
+        if (lane < K) {
+            topk_ids[static_cast<size_t>(t) * K + lane] = id;
+            topk_s[static_cast<size_t>(t) * K + lane] = sv;
+        }
+        if (w_sg != nullptr && lane == 0) {
+            float g = 0.f;
+#pragma unroll
+            for (int w = 0; w < kRouteWaves; ++w) g += gpart[w][q];
+            sgate[t] = 1.f / (1.f + expf(-g));
+        }
+    }
+}
+
+// Candidates from caller-supplied scores: one wave per token.
+__global__ __launch_bounds__(256) void topk_from_scores_kernel(
+    const float* __restrict__ scores, int T, int E, int K, int32_t* __restrict__ topk_ids,
+    float* __restrict__ topk_s) {
+    const int lane = lane_id();
+    const int t = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+    if (t >= T) return;
+    const bool valid = lane < E;
+    const float s = valid ? scores[static_cast<size_t>(t) * E + lane] : 0.f;
+    int id;
+    float sv;
+    wave_topk(s, valid, K, id, sv);
+    if (lane < K) {
+        topk_ids[static_cast<size_t>(t) * K + lane] = id;
+        topk_s[static_cast<size_t>(t) * K + lane] = sv;
+    }
+}
+
+hipError_t launch_route(int dtype, const void* X, const void* Wg, const float* bias,
+                        const void* w_sg, int T, int d, int E, int K, float* scores,
+                        int32_t* topk_ids, float* topk_s, float* sgate, hipStream_t stream) {
+    const dim3 grid((T + kRouteTok - 1) / kRouteTok), block(kRouteWaves * kWave);
+    if (dtype == 0) {
+        hipLaunchKernelGGL(route_kernel<float>, grid, block, 0, stream,
+                           static_cast<const float*>(X), static_cast<const float*>(Wg), bias,
+                           static_cast<const float*>(w_sg), T, d, E, K, scores, topk_ids, topk_s,
+                           sgate);
+    } else {
+        hipLaunchKernelGGL(route_kernel<bf16_t>, grid, block, 0, stream,
+                           static_cast<const bf16_t*>(X), static_cast<const bf16_t*>(Wg), bias,
+                           static_cast<const bf16_t*>(w_sg), T, d, E, K, scores, topk_ids,
+                           topk_s, sgate);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_topk_from_scores(const float* scores, int T, int E, int K, int32_t* topk_ids,
+                                   float* topk_s, hipStream_t stream) {
+    const int waves = 4;
+    const dim3 grid((T + waves - 1) / waves), block(waves * kWave);
+    hipLaunchKernelGGL(topk_from_scores_kernel, grid, block, 0, stream, scores, T, E, K, topk_ids,
+                       topk_s);
+    return hipGetLastError();
+}
+
+}  // namespace allocmoe

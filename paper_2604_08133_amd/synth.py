@@ -89,33 +89,40 @@ def _normal(shape, var: float, name: str, seed: int, layer: int, dtype: torch.dt
 
 
 def make_layer(w: Workload, seed: int = BASE_SEED, layer: int = 0,
-               device: str = "cpu") -> dict:
-    """Draw every tensor of one layer.  Values depend on (seed, layer, tensor
-    name, device kind) only.  Matrices are row-major: Wg [d,E]; W1,W3 [E,d,I];
+               device: str = "cpu", only=None) -> dict:
+    """Draw the tensors of one layer.  Values depend on (seed, layer, tensor
+    name, device kind) and the tensor's shape only, never on which other tensors
+    are drawn.  `only` (a collection of names) restricts what is generated; the
+    rest is None.  Matrices are row-major: X [T,d]; Wg [d,E]; W1,W3 [E,d,I];
     W2 [E,I,d]; Ws1,Ws3 [d,I_shared]; Ws2 [I_shared,d]; w_sg [d]; bias [E] fp32.
     bf16 workloads hold round-to-nearest-even bf16 values."""
     dt = torch.float32 if w.dtype == "f32" else torch.bfloat16
-    out = {
-        "X": _normal((w.T, w.d), 1.0, "X", seed, layer, dt, device),
-        "Wg": _normal((w.d, w.E), 1.0 / w.d, "Wg", seed, layer, dt, device),
-        "W1": _normal((w.E, w.d, w.I), 1.0 / w.d, "W1", seed, layer, dt, device),
-        "W3": _normal((w.E, w.d, w.I), 1.0 / w.d, "W3", seed, layer, dt, device),
-        "W2": _normal((w.E, w.I, w.d), 1.0 / w.I, "W2", seed, layer, dt, device),
-        "bias": None, "Ws1": None, "Ws3": None, "Ws2": None, "w_sg": None,
-    }
+    names = ("X", "Wg", "W1", "W3", "W2", "bias", "Ws1", "Ws3", "Ws2", "w_sg")
+    want = set(names if only is None else only)
+    out = {n: None for n in names}
+
+    def draw(name, shape, var, dtype=dt):
+        if name in want:
+            out[name] = _normal(shape, var, name, seed, layer, dtype, device)
+
+    draw("X", (w.T, w.d), 1.0)
+    draw("Wg", (w.d, w.E), 1.0 / w.d)
+    draw("W1", (w.E, w.d, w.I), 1.0 / w.d)
+    draw("W3", (w.E, w.d, w.I), 1.0 / w.d)
+    draw("W2", (w.E, w.I, w.d), 1.0 / w.I)
     if w.bias_kind == "normal":
-        out["bias"] = _normal((w.E,), 0.5, "bias", seed, layer, torch.float32, device)
-    elif w.bias_kind == "zipf":
+        draw("bias", (w.E,), 0.5, torch.float32)
+    elif w.bias_kind == "zipf" and "bias" in want:
         g = _gen("perm", seed, layer, "cpu")
         perm = torch.randperm(w.E, generator=g)
         out["bias"] = (-1.1 * torch.log(perm.to(torch.float32) + 1.0)).to(device)
     if w.I_shared > 0:
         each = w.I_shared_each or w.I_shared
-        out["Ws1"] = _normal((w.d, w.I_shared), 1.0 / w.d, "Ws1", seed, layer, dt, device)
-        out["Ws3"] = _normal((w.d, w.I_shared), 1.0 / w.d, "Ws3", seed, layer, dt, device)
-        out["Ws2"] = _normal((w.I_shared, w.d), 1.0 / each, "Ws2", seed, layer, dt, device)
+        draw("Ws1", (w.d, w.I_shared), 1.0 / w.d)
+        draw("Ws3", (w.d, w.I_shared), 1.0 / w.d)
+        draw("Ws2", (w.I_shared, w.d), 1.0 / each)
         if w.shared_gate:
-            out["w_sg"] = _normal((w.d,), 1.0 / w.d, "w_sg", seed, layer, dt, device)
+            draw("w_sg", (w.d,), 1.0 / w.d)
     return out
 
 

@@ -1,0 +1,116 @@
+"""GPU parity of the integer path through the C ABI: candidates, Alloc-T keep
+counts and the expert-sorted dispatch must be bit-exact functions of the score
+input (compared with the CPU oracle on identical scores)."""
+import pytest
+import torch
+
+import oracle
+from paper_2604_08133_amd import binding as B
+from paper_2604_08133_amd import synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def gpu_route_dispatch(scores_cpu, K, Kb, budget):
+    T, E = scores_cpu.shape
+    desc = B.make_desc(T, 64, E, 64, K, Kb, budget, "f32")
+    s = scores_cpu.to(DEV)
+    ids = torch.empty((T, K), dtype=torch.int32, device=DEV)
+    vals = torch.empty((T, K), dtype=torch.float32, device=DEV)
+    cnt = torch.empty((T,), dtype=torch.int32, device=DEV)
+    B.allocmoe_route_from_scores(desc, s, ids, vals, cnt)
+    offs = torch.empty((E + 1,), dtype=torch.int32, device=DEV)
+    row_token = torch.full((max(budget, 1),), -7, dtype=torch.int32, device=DEV)
+    row_rank = torch.full((max(budget, 1),), -7, dtype=torch.int32, device=DEV)
+    inv_row = torch.empty((T, K), dtype=torch.int32, device=DEV)
+    ws = torch.empty(B.allocmoe_workspace_layout(desc).scores, dtype=torch.uint8, device=DEV)
+    B.allocmoe_dispatch(desc, ids, cnt, offs, row_token, row_rank, inv_row, ws)
+    torch.cuda.synchronize()
+    return dict(topk_ids=ids.cpu(), topk_s=vals.cpu(), keep_count=cnt.cpu(),
+                expert_offsets=offs.cpu(), row_token=row_token.cpu()[:budget],
+                row_rank=row_rank.cpu()[:budget], inv_row=inv_row.cpu())
+
+
+def oracle_route_dispatch(scores_cpu, K, Kb, budget):
+    ids, vals = oracle.topk(scores_cpu, K)
+    kept, cnt = oracle.alloc_t(vals, Kb, budget)
+    offs, row_token, row_rank, inv_row = oracle.dispatch(ids, kept, scores_cpu.shape[1])
+    return dict(topk_ids=ids, topk_s=vals, keep_count=cnt, expert_offsets=offs,
+                row_token=row_token, row_rank=row_rank, inv_row=inv_row)
+
+
+def assert_same(got, want, tag):
+    for k in want:
+        assert torch.equal(got[k], want[k]), (tag, k)
+
+
+def budgets_for(T, K, Kb):
+    lo, hi = T * Kb, T * K
+    mid = (lo + hi) // 2
+    return sorted({lo, min(hi, lo + 1), mid, min(hi, mid + 7), max(lo, hi - 1), hi})
+
+
+@pytest.mark.parametrize("T,E,K", [(64, 8, 2), (32, 64, 6), (1, 64, 6), (63, 17, 5), (333, 60, 4),
+                                   (1000, 64, 6), (1025, 64, 8), (4096, 64, 6), (8192, 64, 6)])
+@pytest.mark.parametrize("Kb", [0, 1, 2])
+def test_bit_exact_distinct_scores(T, E, K, Kb):
+    if Kb > K:
+        pytest.skip("K_base > K")
+    scores = synth.make_scores(T, E, seed=T + E)
+    for budget in budgets_for(T, K, Kb):
+        print(f"case T={T} E={E} K={K} Kb={Kb} B={budget}", flush=True)
+        assert_same(gpu_route_dispatch(scores, K, Kb, budget),
+                    oracle_route_dispatch(scores, K, Kb, budget), (T, E, K, Kb, budget))
+
+
+@pytest.mark.parametrize("levels", [4, 64, 1024])
+@pytest.mark.parametrize("T,E,K,Kb", [(200, 16, 4, 1), (3000, 64, 6, 1), (3000, 64, 6, 0),
+                                      (2049, 60, 4, 2)])
+def test_bit_exact_with_ties(levels, T, E, K, Kb):
+    scores = synth.make_scores(T, E, seed=levels + T, quantize_levels=levels)
+    for budget in budgets_for(T, K, Kb) + [T * Kb + T // 3]:
+        print(f"ties T={T} E={E} K={K} Kb={Kb} B={budget} levels={levels}", flush=True)
+        assert_same(gpu_route_dispatch(scores, K, Kb, budget),
+                    oracle_route_dispatch(scores, K, Kb, budget), (levels, T, budget))
+
+
+def test_all_scores_equal():
+    T, E, K = 2500, 64, 6
+    scores = torch.full((T, E), 1.0 / E, dtype=torch.float32)
+    for Kb, budget in [(1, T + 1), (1, 3 * T + 11), (0, 17), (2, 5 * T), (1, 6 * T - 1)]:
+        print(f"equal Kb={Kb} B={budget}", flush=True)
+        assert_same(gpu_route_dispatch(scores, K, Kb, budget),
+                    oracle_route_dispatch(scores, K, Kb, budget), (Kb, budget))
+
+
+def test_signed_and_zero_scores():
+    # route_from_scores orders any finite fp32: negatives, -0.0 == +0.0, tiny values
+    g = torch.Generator().manual_seed(12)
+    T, E, K = 500, 32, 5
+    scores = torch.randn((T, E), generator=g)
+    scores[::7, ::3] = 0.0
+    scores[::5, 1::4] = -0.0
+    scores[3::11] = 1e-41          # subnormals
+    for Kb, budget in [(1, 2 * T), (0, T + 3), (2, 4 * T - 5)]:
+        got = gpu_route_dispatch(scores, K, Kb, budget)
+        want = oracle_route_dispatch(scores, K, Kb, budget)
+        assert_same(got, want, (Kb, budget))
+
+
+def test_conservation_on_device():
+    T, E, K = 4096, 64, 6
+    scores = synth.make_scores(T, E, seed=77)
+    for budget in (T, 12288, 20000, T * K):
+        got = gpu_route_dispatch(scores, K, 1, budget)
+        assert int(got["keep_count"].sum()) == budget
+        assert int(got["expert_offsets"][-1]) == budget
+        assert int(got["keep_count"].min()) >= 1 and int(got["keep_count"].max()) <= K
+
+
+def test_budget_errors_reported_by_status():
+    desc = B.make_desc(8, 64, 8, 64, 2, 1, 7, "f32")
+    with pytest.raises(B.AllocMoEError) as e:
+        t = torch.zeros((8, 8), device=DEV)
+        B.allocmoe_route_from_scores(desc, t, t, t, t)
+    assert e.value.status == B.EBUDGET
