@@ -1,0 +1,241 @@
+#!/usr/bin/env python3
+"""Benchmark of the budget-constrained MoE layer forward on one MI355X.
+
+A step is one pass of the whole hot path (route -> Alloc-T selection ->
+dispatch -> SwiGLU expert networks over the selected pairs + shared expert ->
+combine) over one batch of seeded synthetic input that is already resident in
+HBM.  Prints ONE JSON line ("Measurement").
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload decode|prefill|qwen|stack]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+
+
+def parse_args():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=200)
+    p.add_argument("--warmup", type=int, default=20)
+    p.add_argument("--workload", default="decode",
+                   choices=["decode", "prefill", "qwen", "stack"])
+    p.add_argument("--budget-ratio", type=float, default=0.5,
+                   help="layer budget as a fraction of T*K (the metric is quoted at 0.5)")
+    p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--copy-probe", action="store_true",
+                   help="only run a plain device copy of 1 GiB (calibrates the rocprofv3 "
+                        "FETCH_SIZE / WRITE_SIZE counters)")
+    p.add_argument("--cpu-seconds", type=float, default=20.0,
+                   help="rough bound on the oracle's CPU time")
+    return p.parse_args()
+
+
+def workload_for(name: str, ratio: float):
+    from paper_2604_08133_amd import synth
+    if name == "decode":
+        w = synth.deepseek_decode()
+    elif name == "prefill":
+        w = synth.deepseek_prefill()
+    elif name == "qwen":
+        w = synth.qwen_moe()
+    else:
+        w = synth.deepseek_stack_layer(budget=0)
+    return w.with_(budget=int(round(ratio * w.T * w.K)))
+
+
+def traffic_from_profiles(workload: str, kernel: str):
+    """HBM bytes per launch of `kernel` measured with rocprofv3 --pmc, read from
+    the committed summary profiles/pmc_<workload>.txt (line
+    'traffic_bytes_per_launch <kernel> <bytes>'); None if not recorded."""
+    path = os.path.join(ROOT, "profiles", f"pmc_{workload}.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) == 3 and parts[0] == "traffic_bytes_per_launch" and parts[1] == kernel:
+                    return float(parts[2])
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(w, layer, seconds: float):
+    """The oracle as it stands, single-threaded, on a bounded sample of the
+    same workload: Eq. (1) + candidates + Alloc-T + dispatch for all T tokens,
+    Eq. (2) outputs for the first n tokens; tokens/s extrapolated per token for
+    the output part."""
+    import oracle
+    t0 = time.perf_counter()
+    scores = oracle.softmax(oracle.gate_logits(layer["X"], layer["Wg"], layer.get("bias")))
+    ids, s = oracle.topk(scores, w.K)
+    kept, cnt = oracle.alloc_t(s, w.K_base, w.budget)
+    oracle.dispatch(ids, kept, w.E)
+    sg = oracle.shared_gate(layer["X"], layer["w_sg"]) if layer.get("w_sg") is not None else None
+    t_route = time.perf_counter() - t0
+    # output rows: time one token, then as many as fit the bound
+    done, t_out = 0, 0.0
+    n = 1
+    while done < w.T:
+        toks = list(range(done, min(w.T, done + n)))
+        t1 = time.perf_counter()
+        oracle.moe_eq2(layer, ids, s, kept, sg, dense=False, tokens=toks)
+        t_out += time.perf_counter() - t1
+        done += len(toks)
+        per_tok = t_out / done
+        left = seconds - t_route - t_out
+        if left < per_tok:
+            break
+        n = max(1, min(w.T - done, int(left / per_tok / 2) or 1))
+    total = t_route + (t_out / done) * w.T
+    return {
+        "value": w.T / total, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+        "sample": (f"routing+selection+dispatch for all {w.T} tokens ({t_route:.2f} s) + Eq.(2) "
+                   f"outputs of the first {done} tokens ({t_out:.2f} s), output time scaled to "
+                   f"{w.T} tokens"),
+    }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding or collectives are part "
+              "of it); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2604_08133_amd import binding as B
+    from paper_2604_08133_amd import synth
+    from paper_2604_08133_amd.layer import DeviceLayer
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    B.load()   # fails loudly if the HIP library is missing
+    torch.cuda.set_device(0)
+    if args.copy_probe:
+        n = 1 << 30
+        src = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(3)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes": n, "launches": 5}))
+        return
+
+    w = workload_for(args.workload, args.budget_ratio)
+    on_cpu = w.T * w.d <= (1 << 24) and args.workload in ("decode",)
+    # Inputs: generated on the CPU for the small workload (the oracle baseline
+    # needs the same bytes), on the GPU for the big ones.
+    layer_cpu = synth.make_layer(w, device="cpu") if on_cpu else None
+    if layer_cpu is not None:
+        dev = DeviceLayer(w, layer_cpu)
+    else:
+        dev = DeviceLayer(w, synth.make_layer(w, device="cuda"))
+    desc = dev.desc()
+    ws = dev.workspace(desc)
+    Y = torch.empty((w.T, w.d), dtype=dev.dtype, device=dev.device)
+
+    def step():
+        B.allocmoe_moe_forward(desc, dev.X, dev.weights, Y, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+
+    # per-kernel durations: the same steps again through the event-instrumented
+    # entry point (HIP events recorded by the library on the launch stream)
+    stage_ms = [0.0] * len(B.STAGES)
+    for _ in range(args.steps):
+        ms = B.allocmoe_moe_forward_timed(desc, dev.X, dev.weights, Y, ws)
+        stage_ms = [a + b for a, b in zip(stage_ms, ms)]
+    stage_ms = [v / args.steps for v in stage_ms]
+    stages = dict(zip(B.STAGES, stage_ms))
+
+    mid = dev.intermediates()
+    offs = mid["expert_offsets"].cpu()
+    rows_per_expert = (offs[1:] - offs[:-1])
+    n_active = int((rows_per_expert > 0).sum())
+    Bn = int(offs[-1])
+    assert Bn == w.budget, "selected pairs != layer budget"
+
+    # ---- roofline of the dominant kernel
+    d, I, Is, T = w.d, w.I, w.I_shared, w.T
+    ffn1_bytes = n_active * 2 * d * I * 2 + Bn * (d * 2 + I * 2)     # W1,W3 once per active expert; x in, H out
+    ffn1_flops = Bn * 2 * d * (2 * I)
+    dom = "ffn1_routed"
+    dom_ms = stages[dom]
+    kernel_name = "ffn_bf16_stream_kernel<true>"
+    if args.workload == "decode":
+        roof = {"bound": "hbm", "achieved": ffn1_bytes / (dom_ms * 1e-3) / 1e9,
+                "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+    else:
+        roof = {"bound": "mfma", "achieved": ffn1_flops / (dom_ms * 1e-3) / 1e12,
+                "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = traffic_from_profiles(args.workload, dom)
+    roof["kernel"] = kernel_name
+    roof["kernel_ms"] = dom_ms
+    roof["algorithmic_bytes"] = ffn1_bytes
+    roof["algorithmic_flops"] = ffn1_flops
+
+    # whole-step algorithmic traffic and work (context for the step time)
+    step_bytes = (n_active * 3 * d * I * 2 + 3 * d * Is * 2          # expert + shared weights
+                  + T * d * 2 * 2 + d * w.E * 2                      # X (gate), Y, Wg
+                  + Bn * (d * 2 + 2 * I * 2 + 2 * d * 4)             # x gather, H w+r, O w+r
+                  + (T * (d * 2 + 2 * Is * 2 + 2 * d * 4) if Is else 0))
+    step_flops = Bn * 6 * d * I + T * 6 * d * Is + T * 2 * d * w.E
+    step_info = {
+        "algorithmic_bytes": step_bytes, "algorithmic_flops": step_flops,
+        "hbm_frac": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "mfma_frac": step_flops / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+        "active_experts": n_active,
+        "stage_ms": {k: round(v, 5) for k, v in stages.items()},
+    }
+
+    out = {
+        "metric": "budgeted MoE-layer tokens/s at 0.5x budget",
+        "value": w.T / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "T": w.T, "d": w.d, "E": w.E, "I": w.I, "K": w.K,
+                   "K_base": w.K_base, "budget": w.budget, "budget_ratio": args.budget_ratio,
+                   "I_shared": w.I_shared, "weights": "re-tiled once by allocmoe_pack_weights, "
+                   "outside the timed region"},
+        "roofline": roof,
+        "step": step_info,
+    }
+    if not args.no_cpu_baseline:
+        if layer_cpu is None:
+            # bounded sample for the big workloads: the same shapes at T = 32 tokens
+            ws_small = w.with_(T=32, budget=int(round(args.budget_ratio * 32 * w.K)))
+            cb = cpu_baseline(ws_small, synth.make_layer(ws_small, device="cpu"), args.cpu_seconds)
+            cb["sample"] = f"same layer shapes at T=32 tokens: " + cb["sample"]
+        else:
+            cb = cpu_baseline(w, layer_cpu, args.cpu_seconds)
+        out["cpu_baseline"] = cb
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -159,6 +159,29 @@ allocmoe_status allocmoe_moe_forward(const allocmoe_layer_desc *desc, const void
                                      const allocmoe_weights *w, void *Y, void *ws,
                                      size_t ws_bytes, allocmoe_stream stream);
 
+/* Stages of allocmoe_moe_forward, in launch order (one kernel each). */
+typedef enum {
+    ALLOCMOE_STAGE_ROUTE = 0,       /* steps 1-2: gate, softmax, sorted candidates        */
+    ALLOCMOE_STAGE_PLAN = 1,        /* steps 3-4: Alloc-T selection, dispatch, tile map    */
+    ALLOCMOE_STAGE_FFN1_ROUTED = 2, /* step 5: H = silu(x W1) * (x W3) over selected rows  */
+    ALLOCMOE_STAGE_FFN2_ROUTED = 3, /* step 5: O = H W2                                    */
+    ALLOCMOE_STAGE_FFN1_SHARED = 4, /* step 5: shared expert, first half                   */
+    ALLOCMOE_STAGE_FFN2_SHARED = 5, /* step 5: shared expert, second half                  */
+    ALLOCMOE_STAGE_COMBINE = 6,     /* step 6: Eq. (2)                                     */
+    ALLOCMOE_N_STAGES = 7
+} allocmoe_stage;
+
+/* Measurement variant of allocmoe_moe_forward: same work, same kernels, same
+ * launch configuration, but a HIP event is recorded on the stream around every
+ * stage; the call then WAITS for the last event (the one exception to the
+ * no-synchronisation rule) and writes the stage durations in milliseconds to
+ * stage_ms[ALLOCMOE_N_STAGES] (host memory).  The events are host objects the
+ * library creates on first use and keeps; not thread-safe; for benchmarking. */
+allocmoe_status allocmoe_moe_forward_timed(const allocmoe_layer_desc *desc, const void *X,
+                                           const allocmoe_weights *w, void *Y, void *ws,
+                                           size_t ws_bytes, allocmoe_stream stream,
+                                           float *stage_ms);
+
 const char *allocmoe_status_string(allocmoe_status status);
 
 #ifdef __cplusplus

@@ -21,8 +21,10 @@ F32, BF16 = 0, 1
 EXPORTS = [
     "allocmoe_workspace_bytes", "allocmoe_workspace_layout", "allocmoe_packed_bytes",
     "allocmoe_pack_weights", "allocmoe_route", "allocmoe_route_from_scores",
-    "allocmoe_dispatch", "allocmoe_moe_forward", "allocmoe_status_string",
+    "allocmoe_dispatch", "allocmoe_moe_forward", "allocmoe_moe_forward_timed",
+    "allocmoe_status_string",
 ]
+STAGES = ["route", "plan", "ffn1_routed", "ffn2_routed", "ffn1_shared", "ffn2_shared", "combine"]
 
 
 class LayerDesc(ctypes.Structure):
@@ -168,6 +170,17 @@ def allocmoe_moe_forward(desc: LayerDesc, X, w: Weights, Y, ws: torch.Tensor, st
     _check(load().allocmoe_moe_forward(ctypes.byref(desc), _ptr(X), ctypes.byref(w), _ptr(Y),
                                        _ptr(ws), ctypes.c_size_t(ws.numel() * ws.element_size()),
                                        _stream(stream)), "allocmoe_moe_forward")
+
+
+def allocmoe_moe_forward_timed(desc: LayerDesc, X, w: Weights, Y, ws: torch.Tensor,
+                               stream=None) -> list:
+    """Returns the per-stage durations in ms (order: STAGES); synchronises."""
+    ms = (ctypes.c_float * len(STAGES))()
+    _check(load().allocmoe_moe_forward_timed(ctypes.byref(desc), _ptr(X), ctypes.byref(w),
+                                             _ptr(Y), _ptr(ws),
+                                             ctypes.c_size_t(ws.numel() * ws.element_size()),
+                                             _stream(stream), ms), "allocmoe_moe_forward_timed")
+    return list(ms)
 
 
 # ------------------------------------------------ conveniences for tests/bench

@@ -227,9 +227,19 @@ allocmoe_status allocmoe_dispatch(const allocmoe_layer_desc* desc, const int32_t
     return ALLOCMOE_OK;
 }
 
-allocmoe_status allocmoe_moe_forward(const allocmoe_layer_desc* desc, const void* X,
-                                     const allocmoe_weights* w, void* Y, void* ws,
-                                     size_t ws_bytes, allocmoe_stream stream_) {
+}  // extern "C"
+
+namespace {
+
+// Records ev[i] (when ev is not null) on the stream before stage i.
+#define ALLOCMOE_MARK(i)                                                  \
+    do {                                                                  \
+        if (ev != nullptr) ALLOCMOE_TRY(hipEventRecord(ev[i], stream));   \
+    } while (0)
+
+allocmoe_status forward_impl(const allocmoe_layer_desc* desc, const void* X,
+                             const allocmoe_weights* w, void* Y, void* ws, size_t ws_bytes,
+                             allocmoe_stream stream_, hipEvent_t* ev) {
     allocmoe_ws_layout L;
     const allocmoe_status st = layout_of(desc, &L);
     if (st != ALLOCMOE_OK) return st;
@@ -268,10 +278,12 @@ allocmoe_status allocmoe_moe_forward(const allocmoe_layer_desc* desc, const void
     float* Os = Is ? at<float>(base, L.Os) : nullptr;
 
     // steps 1-2: scores and sorted candidates
+    ALLOCMOE_MARK(ALLOCMOE_STAGE_ROUTE);
     ALLOCMOE_TRY(launch_route(desc->dtype, X, w->Wg, w->gate_bias,
                               desc->shared_gate ? w->w_sg : nullptr, T, d, E, K, scores, topk_ids,
                               topk_s, sgate, stream));
     // steps 3-4: Alloc-T selection, dispatch, tile map
+    ALLOCMOE_MARK(ALLOCMOE_STAGE_PLAN);
     ALLOCMOE_TRY(launch_plan(topk_s, topk_ids, T, K, desc->K_base, B, E, keep_count,
                              expert_offsets, row_token, row_rank, inv_row,
                              at<uint64_t>(scr, s.words), at<int32_t>(scr, s.prefix),
@@ -281,40 +293,80 @@ allocmoe_status allocmoe_moe_forward(const allocmoe_layer_desc* desc, const void
         const PackedLayout p = packed_of(desc);
         const uint16_t* pk = static_cast<const uint16_t*>(w->packed);
         const size_t dd = d, II = I, SS = Is;
-        if (B > 0) {
+        ALLOCMOE_MARK(ALLOCMOE_STAGE_FFN1_ROUTED);
+        if (B > 0)
             ALLOCMOE_TRY(launch_ffn_bf16_stream(true, X, d, row_token, pk + p.p13, 2 * dd * II, d,
                                                 I, tile_info, s.max_tiles, 0, H, I, stream));
+        ALLOCMOE_MARK(ALLOCMOE_STAGE_FFN2_ROUTED);
+        if (B > 0)
             ALLOCMOE_TRY(launch_ffn_bf16_stream(false, H, I, nullptr, pk + p.p2, II * dd, I, d,
                                                 tile_info, s.max_tiles, 0, O, d, stream));
-        }
-        if (Is) {
+        ALLOCMOE_MARK(ALLOCMOE_STAGE_FFN1_SHARED);
+        if (Is)
             ALLOCMOE_TRY(launch_ffn_bf16_stream(true, X, d, nullptr, pk + p.ps13, 2 * dd * SS, d,
                                                 Is, nullptr, 0, T, Hs, Is, stream));
+        ALLOCMOE_MARK(ALLOCMOE_STAGE_FFN2_SHARED);
+        if (Is)
             ALLOCMOE_TRY(launch_ffn_bf16_stream(false, Hs, Is, nullptr, pk + p.ps2, SS * dd, Is, d,
                                                 nullptr, 0, T, Os, d, stream));
-        }
     } else {
         const float* Xf = static_cast<const float*>(X);
-        if (B > 0) {
+        ALLOCMOE_MARK(ALLOCMOE_STAGE_FFN1_ROUTED);
+        if (B > 0)
             ALLOCMOE_TRY(launch_ffn_f32(true, Xf, d, row_token, static_cast<const float*>(w->W1),
                                         static_cast<const float*>(w->W3), d, I, tile_info,
                                         s.max_tiles, 0, static_cast<float*>(H), I, stream));
+        ALLOCMOE_MARK(ALLOCMOE_STAGE_FFN2_ROUTED);
+        if (B > 0)
             ALLOCMOE_TRY(launch_ffn_f32(false, static_cast<const float*>(H), I, nullptr,
                                         static_cast<const float*>(w->W2), nullptr, I, d, tile_info,
                                         s.max_tiles, 0, O, d, stream));
-        }
-        if (Is) {
+        ALLOCMOE_MARK(ALLOCMOE_STAGE_FFN1_SHARED);
+        if (Is)
             ALLOCMOE_TRY(launch_ffn_f32(true, Xf, d, nullptr, static_cast<const float*>(w->Ws1),
                                         static_cast<const float*>(w->Ws3), d, Is, nullptr, 0, T,
                                         static_cast<float*>(Hs), Is, stream));
+        ALLOCMOE_MARK(ALLOCMOE_STAGE_FFN2_SHARED);
+        if (Is)
             ALLOCMOE_TRY(launch_ffn_f32(false, static_cast<const float*>(Hs), Is, nullptr,
                                         static_cast<const float*>(w->Ws2), nullptr, Is, d, nullptr,
                                         0, T, Os, d, stream));
-        }
     }
     // step 6: Eq. (2)
+    ALLOCMOE_MARK(ALLOCMOE_STAGE_COMBINE);
     ALLOCMOE_TRY(launch_combine(desc->dtype, O, Os, inv_row, topk_s, keep_count, sgate, T, d, K, Y,
                                 stream));
+    ALLOCMOE_MARK(ALLOCMOE_N_STAGES);
+    return ALLOCMOE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+allocmoe_status allocmoe_moe_forward(const allocmoe_layer_desc* desc, const void* X,
+                                     const allocmoe_weights* w, void* Y, void* ws,
+                                     size_t ws_bytes, allocmoe_stream stream) {
+    return forward_impl(desc, X, w, Y, ws, ws_bytes, stream, nullptr);
+}
+
+allocmoe_status allocmoe_moe_forward_timed(const allocmoe_layer_desc* desc, const void* X,
+                                           const allocmoe_weights* w, void* Y, void* ws,
+                                           size_t ws_bytes, allocmoe_stream stream,
+                                           float* stage_ms) {
+    if (stage_ms == nullptr) return ALLOCMOE_EINVAL;
+    // events are host-side objects, created once per process and reused
+    static hipEvent_t ev[ALLOCMOE_N_STAGES + 1];
+    static bool have_events = false;
+    if (!have_events) {
+        for (int i = 0; i <= ALLOCMOE_N_STAGES; ++i) ALLOCMOE_TRY(hipEventCreate(&ev[i]));
+        have_events = true;
+    }
+    const allocmoe_status st = forward_impl(desc, X, w, Y, ws, ws_bytes, stream, ev);
+    if (st != ALLOCMOE_OK) return st;
+    ALLOCMOE_TRY(hipEventSynchronize(ev[ALLOCMOE_N_STAGES]));
+    for (int i = 0; i < ALLOCMOE_N_STAGES; ++i)
+        ALLOCMOE_TRY(hipEventElapsedTime(&stage_ms[i], ev[i], ev[i + 1]));
     return ALLOCMOE_OK;
 }
 
