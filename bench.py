@@ -178,9 +178,12 @@ def main():
 
     # ---- roofline of the dominant kernel
     d, I, Is, T = w.d, w.I, w.I_shared, w.T
-    ffn1_bytes = n_active * 2 * d * I * 2 + Bn * (d * 2 + I * 2)     # W1,W3 once per active expert; x in, H out
-    ffn1_flops = Bn * 2 * d * (2 * I)
-    dom = "ffn1_routed"
+    # ffn1 launch = routed rows + shared expert: W1,W3 once per active expert and
+    # once for the shared expert; x rows in, H rows out
+    ffn1_bytes = (n_active * 2 * d * I * 2 + Bn * (d * 2 + I * 2)
+                  + (2 * d * Is * 2 + T * (d * 2 + Is * 2) if Is else 0))
+    ffn1_flops = Bn * 2 * d * (2 * I) + T * 2 * d * (2 * Is)
+    dom = "ffn1"
     dom_ms = stages[dom]
     kernel_name = "ffn_bf16_stream_kernel<true>"
     if args.workload == "decode":

@@ -159,16 +159,14 @@ allocmoe_status allocmoe_moe_forward(const allocmoe_layer_desc *desc, const void
                                      const allocmoe_weights *w, void *Y, void *ws,
                                      size_t ws_bytes, allocmoe_stream stream);
 
-/* Stages of allocmoe_moe_forward, in launch order (one kernel each). */
+/* Stages of allocmoe_moe_forward, in launch order. */
 typedef enum {
-    ALLOCMOE_STAGE_ROUTE = 0,       /* steps 1-2: gate, softmax, sorted candidates        */
-    ALLOCMOE_STAGE_PLAN = 1,        /* steps 3-4: Alloc-T selection, dispatch, tile map    */
-    ALLOCMOE_STAGE_FFN1_ROUTED = 2, /* step 5: H = silu(x W1) * (x W3) over selected rows  */
-    ALLOCMOE_STAGE_FFN2_ROUTED = 3, /* step 5: O = H W2                                    */
-    ALLOCMOE_STAGE_FFN1_SHARED = 4, /* step 5: shared expert, first half                   */
-    ALLOCMOE_STAGE_FFN2_SHARED = 5, /* step 5: shared expert, second half                  */
-    ALLOCMOE_STAGE_COMBINE = 6,     /* step 6: Eq. (2)                                     */
-    ALLOCMOE_N_STAGES = 7
+    ALLOCMOE_STAGE_ROUTE = 0,   /* steps 1-2: gate, softmax, sorted candidates              */
+    ALLOCMOE_STAGE_PLAN = 1,    /* steps 3-4: Alloc-T selection, dispatch, tile map          */
+    ALLOCMOE_STAGE_FFN1 = 2,    /* step 5: H = silu(x W1) * (x W3), selected rows + shared   */
+    ALLOCMOE_STAGE_FFN2 = 3,    /* step 5: O = H W2, selected rows + shared                  */
+    ALLOCMOE_STAGE_COMBINE = 4, /* step 6: Eq. (2)                                           */
+    ALLOCMOE_N_STAGES = 5
 } allocmoe_stage;
 
 /* Measurement variant of allocmoe_moe_forward: same work, same kernels, same

@@ -24,7 +24,7 @@ EXPORTS = [
     "allocmoe_dispatch", "allocmoe_moe_forward", "allocmoe_moe_forward_timed",
     "allocmoe_status_string",
 ]
-STAGES = ["route", "plan", "ffn1_routed", "ffn2_routed", "ffn1_shared", "ffn2_shared", "combine"]
+STAGES = ["route", "plan", "ffn1", "ffn2", "combine"]
 
 
 class LayerDesc(ctypes.Structure):

@@ -85,7 +85,7 @@ allocmoe_status layout_of(const allocmoe_layer_desc* d, allocmoe_ws_layout* L) {
 }
 
 struct PackedLayout {   // element offsets inside the packed buffer
-    size_t p13, p2, ps13, ps2, total_elems;
+    size_t p13, p2, ps13, ps2, gate, total_elems;
 };
 
 PackedLayout packed_of(const allocmoe_layer_desc* d) {
@@ -95,7 +95,8 @@ PackedLayout packed_of(const allocmoe_layer_desc* d) {
     p.p2 = p.p13 + E * 2 * dd * I;
     p.ps13 = p.p2 + E * I * dd;
     p.ps2 = p.ps13 + 2 * dd * Is;
-    p.total_elems = p.ps2 + Is * dd;
+    p.gate = p.ps2 + Is * dd;
+    p.total_elems = p.gate + gate_packed_elems(d->d);
     return p;
 }
 
@@ -156,8 +157,9 @@ allocmoe_status allocmoe_pack_weights(const allocmoe_layer_desc* desc,
     const allocmoe_status st = check_desc(desc);
     if (st != ALLOCMOE_OK) return st;
     if (desc->dtype != ALLOCMOE_BF16 || w == nullptr || packed == nullptr) return ALLOCMOE_EINVAL;
-    if (!w->W1 || !w->W3 || !w->W2) return ALLOCMOE_EINVAL;
+    if (!w->Wg || !w->W1 || !w->W3 || !w->W2) return ALLOCMOE_EINVAL;
     if (desc->I_shared && (!w->Ws1 || !w->Ws3 || !w->Ws2)) return ALLOCMOE_EINVAL;
+    if (desc->shared_gate && !w->w_sg) return ALLOCMOE_EINVAL;
     const PackedLayout p = packed_of(desc);
     if (packed_bytes < p.total_elems * 2 || !aligned(packed, kAlign)) return ALLOCMOE_EWORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
@@ -167,6 +169,8 @@ allocmoe_status allocmoe_pack_weights(const allocmoe_layer_desc* desc,
     ALLOCMOE_TRY(launch_pack_b(w->W1, E, d, I, out + p.p13, 2 * dd * II, 2 * dd * 32, 0, stream));
     ALLOCMOE_TRY(launch_pack_b(w->W3, E, d, I, out + p.p13, 2 * dd * II, 2 * dd * 32, dd * 32, stream));
     ALLOCMOE_TRY(launch_pack_b(w->W2, E, I, d, out + p.p2, II * dd, II * 32, 0, stream));
+    ALLOCMOE_TRY(launch_pack_gate(w->Wg, desc->shared_gate ? w->w_sg : nullptr, d, E, out + p.gate,
+                                  stream));
     if (Is) {
         const size_t SS = Is;
         ALLOCMOE_TRY(launch_pack_b(w->Ws1, 1, d, Is, out + p.ps13, 2 * dd * SS, 2 * dd * 32, 0, stream));
@@ -186,8 +190,15 @@ allocmoe_status allocmoe_route(const allocmoe_layer_desc* desc, const void* X,
     (void)ws;
     (void)ws_bytes;   // the selection runs out of LDS; no device scratch needed here
     hipStream_t stream = static_cast<hipStream_t>(stream_);
-    ALLOCMOE_TRY(launch_route(desc->dtype, X, w->Wg, w->gate_bias, nullptr, desc->T, desc->d,
-                              desc->E, desc->K, scores, topk_ids, topk_s, nullptr, stream));
+    if (desc->dtype == ALLOCMOE_BF16 && w->packed != nullptr) {
+        if (!aligned(w->packed, kAlign) || !aligned(X, 16)) return ALLOCMOE_EINVAL;
+        const uint16_t* gp = static_cast<const uint16_t*>(w->packed) + packed_of(desc).gate;
+        ALLOCMOE_TRY(launch_route_mfma(X, gp, w->gate_bias, false, desc->T, desc->d, desc->E,
+                                       desc->K, scores, topk_ids, topk_s, nullptr, stream));
+    } else {
+        ALLOCMOE_TRY(launch_route(desc->dtype, X, w->Wg, w->gate_bias, nullptr, desc->T, desc->d,
+                                  desc->E, desc->K, scores, topk_ids, topk_s, nullptr, stream));
+    }
     ALLOCMOE_TRY(launch_select(topk_s, desc->T, desc->K, desc->K_base, desc->budget, keep_count,
                                stream));
     return ALLOCMOE_OK;
@@ -279,9 +290,15 @@ allocmoe_status forward_impl(const allocmoe_layer_desc* desc, const void* X,
 
     // steps 1-2: scores and sorted candidates
     ALLOCMOE_MARK(ALLOCMOE_STAGE_ROUTE);
-    ALLOCMOE_TRY(launch_route(desc->dtype, X, w->Wg, w->gate_bias,
-                              desc->shared_gate ? w->w_sg : nullptr, T, d, E, K, scores, topk_ids,
-                              topk_s, sgate, stream));
+    if (bf16) {
+        const uint16_t* gp = static_cast<const uint16_t*>(w->packed) + packed_of(desc).gate;
+        ALLOCMOE_TRY(launch_route_mfma(X, gp, w->gate_bias, desc->shared_gate != 0, T, d, E, K,
+                                       scores, topk_ids, topk_s, sgate, stream));
+    } else {
+        ALLOCMOE_TRY(launch_route(desc->dtype, X, w->Wg, w->gate_bias,
+                                  desc->shared_gate ? w->w_sg : nullptr, T, d, E, K, scores,
+                                  topk_ids, topk_s, sgate, stream));
+    }
     // steps 3-4: Alloc-T selection, dispatch, tile map
     ALLOCMOE_MARK(ALLOCMOE_STAGE_PLAN);
     ALLOCMOE_TRY(launch_plan(topk_s, topk_ids, T, K, desc->K_base, B, E, keep_count,
@@ -293,40 +310,41 @@ allocmoe_status forward_impl(const allocmoe_layer_desc* desc, const void* X,
         const PackedLayout p = packed_of(desc);
         const uint16_t* pk = static_cast<const uint16_t*>(w->packed);
         const size_t dd = d, II = I, SS = Is;
-        ALLOCMOE_MARK(ALLOCMOE_STAGE_FFN1_ROUTED);
-        if (B > 0)
-            ALLOCMOE_TRY(launch_ffn_bf16_stream(true, X, d, row_token, pk + p.p13, 2 * dd * II, d,
-                                                I, tile_info, s.max_tiles, 0, H, I, stream));
-        ALLOCMOE_MARK(ALLOCMOE_STAGE_FFN2_ROUTED);
-        if (B > 0)
-            ALLOCMOE_TRY(launch_ffn_bf16_stream(false, H, I, nullptr, pk + p.p2, II * dd, I, d,
-                                                tile_info, s.max_tiles, 0, O, d, stream));
-        ALLOCMOE_MARK(ALLOCMOE_STAGE_FFN1_SHARED);
-        if (Is)
-            ALLOCMOE_TRY(launch_ffn_bf16_stream(true, X, d, nullptr, pk + p.ps13, 2 * dd * SS, d,
-                                                Is, nullptr, 0, T, Hs, Is, stream));
-        ALLOCMOE_MARK(ALLOCMOE_STAGE_FFN2_SHARED);
-        if (Is)
-            ALLOCMOE_TRY(launch_ffn_bf16_stream(false, Hs, Is, nullptr, pk + p.ps2, SS * dd, Is, d,
-                                                nullptr, 0, T, Os, d, stream));
+        // routed rows and the shared expert's rows share one launch per half
+        StreamGroup r1, s1, r2, s2;
+        if (B > 0) {
+            r1.A = X; r1.lda = d; r1.row_map = row_token; r1.Bp = pk + p.p13;
+            r1.group_stride = 2 * dd * II; r1.Kd = d; r1.N = I; r1.tile_info = tile_info;
+            r1.max_tiles = s.max_tiles; r1.C = H; r1.ldc = I;
+            r2.A = H; r2.lda = I; r2.Bp = pk + p.p2; r2.group_stride = II * dd; r2.Kd = I;
+            r2.N = d; r2.tile_info = tile_info; r2.max_tiles = s.max_tiles; r2.C = O; r2.ldc = d;
+        }
+        if (Is) {
+            s1.A = X; s1.lda = d; s1.Bp = pk + p.ps13; s1.group_stride = 2 * dd * SS; s1.Kd = d;
+            s1.N = Is; s1.M_dense = T; s1.C = Hs; s1.ldc = Is;
+            s2.A = Hs; s2.lda = Is; s2.Bp = pk + p.ps2; s2.group_stride = SS * dd; s2.Kd = Is;
+            s2.N = d; s2.M_dense = T; s2.C = Os; s2.ldc = d;
+        }
+        ALLOCMOE_MARK(ALLOCMOE_STAGE_FFN1);
+        ALLOCMOE_TRY(launch_ffn_bf16_stream(true, r1, s1, stream));
+        ALLOCMOE_MARK(ALLOCMOE_STAGE_FFN2);
+        ALLOCMOE_TRY(launch_ffn_bf16_stream(false, r2, s2, stream));
     } else {
         const float* Xf = static_cast<const float*>(X);
-        ALLOCMOE_MARK(ALLOCMOE_STAGE_FFN1_ROUTED);
+        ALLOCMOE_MARK(ALLOCMOE_STAGE_FFN1);
         if (B > 0)
             ALLOCMOE_TRY(launch_ffn_f32(true, Xf, d, row_token, static_cast<const float*>(w->W1),
                                         static_cast<const float*>(w->W3), d, I, tile_info,
                                         s.max_tiles, 0, static_cast<float*>(H), I, stream));
-        ALLOCMOE_MARK(ALLOCMOE_STAGE_FFN2_ROUTED);
-        if (B > 0)
-            ALLOCMOE_TRY(launch_ffn_f32(false, static_cast<const float*>(H), I, nullptr,
-                                        static_cast<const float*>(w->W2), nullptr, I, d, tile_info,
-                                        s.max_tiles, 0, O, d, stream));
-        ALLOCMOE_MARK(ALLOCMOE_STAGE_FFN1_SHARED);
         if (Is)
             ALLOCMOE_TRY(launch_ffn_f32(true, Xf, d, nullptr, static_cast<const float*>(w->Ws1),
                                         static_cast<const float*>(w->Ws3), d, Is, nullptr, 0, T,
                                         static_cast<float*>(Hs), Is, stream));
-        ALLOCMOE_MARK(ALLOCMOE_STAGE_FFN2_SHARED);
+        ALLOCMOE_MARK(ALLOCMOE_STAGE_FFN2);
+        if (B > 0)
+            ALLOCMOE_TRY(launch_ffn_f32(false, static_cast<const float*>(H), I, nullptr,
+                                        static_cast<const float*>(w->W2), nullptr, I, d, tile_info,
+                                        s.max_tiles, 0, O, d, stream));
         if (Is)
             ALLOCMOE_TRY(launch_ffn_f32(false, static_cast<const float*>(Hs), Is, nullptr,
                                         static_cast<const float*>(w->Ws2), nullptr, Is, d, nullptr,

@@ -28,15 +28,25 @@ constexpr int kStreamUnroll = 8;
 __device__ __forceinline__ int acc_row(int r, int l) { return 8 * (r / 4) + 4 * (l / 32) + (r % 4); }
 
 template <bool SWIGLU>
-__global__ __launch_bounds__(kStreamWaves* kWave) void ffn_bf16_stream_kernel(
-    const bf16_t* __restrict__ A, int lda, const int32_t* __restrict__ row_map,
-    const bf16_t* __restrict__ Bp, size_t group_stride, int Kd, int N,
-    const int32_t* __restrict__ tile_info, int M_dense, void* __restrict__ Cv, int ldc) {
+__global__ __launch_bounds__(kStreamWaves* kWave) void ffn_bf16_stream_kernel(StreamGroup g0,
+                                                                             StreamGroup g1) {
     constexpr int NACC = SWIGLU ? 2 : 1;
     __shared__ float red[kStreamWaves][NACC][16][kWave];
 
+    // the grid is the routed group's workgroups followed by the shared expert's
+    const bool first = static_cast<int64_t>(blockIdx.x) < g0.n_wg;
+    const StreamGroup& g = first ? g0 : g1;
+    const int bid = first ? blockIdx.x : blockIdx.x - static_cast<unsigned>(g0.n_wg);
+    const bf16_t* __restrict__ A = static_cast<const bf16_t*>(g.A);
+    const bf16_t* __restrict__ Bp = static_cast<const bf16_t*>(g.Bp);
+    const int32_t* __restrict__ row_map = g.row_map;
+    const int32_t* __restrict__ tile_info = g.tile_info;
+    const int lda = g.lda, Kd = g.Kd, N = g.N, ldc = g.ldc, M_dense = g.M_dense;
+    const size_t group_stride = g.group_stride;
+    void* Cv = g.C;
+
     const int n_blocks = N / 32;
-    const int tile = blockIdx.x / n_blocks, nb = blockIdx.x % n_blocks;
+    const int tile = bid / n_blocks, nb = bid % n_blocks;
     int e, row0, rows;
     if (tile_info != nullptr) {
         if (tile >= tile_info[0]) return;
@@ -128,23 +138,21 @@ __global__ __launch_bounds__(kStreamWaves* kWave) void ffn_bf16_stream_kernel(
     }
 }
 
-hipError_t launch_ffn_bf16_stream(bool swiglu, const void* A, int lda, const int32_t* row_map,
-                                  const void* Bp, size_t group_stride_elems, int Kd, int N,
-                                  const int32_t* tile_info, int64_t max_tiles, int M_dense,
-                                  void* C, int ldc, hipStream_t stream) {
-    const int64_t tiles = tile_info ? max_tiles : (M_dense + 31) / 32;
-    if (tiles <= 0) return hipSuccess;
-    const dim3 grid(static_cast<unsigned>(tiles * (N / 32))), block(kStreamWaves * kWave);
+hipError_t launch_ffn_bf16_stream(bool swiglu, StreamGroup routed, StreamGroup shared,
+                                  hipStream_t stream) {
+    auto count = [](StreamGroup& g) {
+        const int64_t tiles = g.A == nullptr ? 0 : (g.tile_info ? g.max_tiles : (g.M_dense + 31) / 32);
+        g.n_wg = tiles * (g.N / 32);
+    };
+    count(routed);
+    count(shared);
+    const int64_t total = routed.n_wg + shared.n_wg;
+    if (total <= 0) return hipSuccess;
+    const dim3 grid(static_cast<unsigned>(total)), block(kStreamWaves * kWave);
     if (swiglu)
-        hipLaunchKernelGGL(ffn_bf16_stream_kernel<true>, grid, block, 0, stream,
-                           static_cast<const bf16_t*>(A), lda, row_map,
-                           static_cast<const bf16_t*>(Bp), group_stride_elems, Kd, N, tile_info,
-                           M_dense, C, ldc);
+        hipLaunchKernelGGL(ffn_bf16_stream_kernel<true>, grid, block, 0, stream, routed, shared);
     else
-        hipLaunchKernelGGL(ffn_bf16_stream_kernel<false>, grid, block, 0, stream,
-                           static_cast<const bf16_t*>(A), lda, row_map,
-                           static_cast<const bf16_t*>(Bp), group_stride_elems, Kd, N, tile_info,
-                           M_dense, C, ldc);
+        hipLaunchKernelGGL(ffn_bf16_stream_kernel<false>, grid, block, 0, stream, routed, shared);
     return hipGetLastError();
 }
 

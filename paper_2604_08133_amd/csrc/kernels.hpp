@@ -19,6 +19,15 @@ inline size_t tile_info_ints(int64_t max_tiles) { return 4 + 4 * static_cast<siz
 hipError_t launch_route(int dtype, const void* X, const void* Wg, const float* bias,
                         const void* w_sg, int T, int d, int E, int K, float* scores,
                         int32_t* topk_ids, float* topk_s, float* sgate, hipStream_t stream);
+// bf16 gate GEMM on the matrix cores from the re-tiled gate matrix
+// (kGateBlocks 16-column blocks: 64 expert columns + the shared-gate column)
+constexpr int kGateBlocks = 5;
+inline size_t gate_packed_elems(int d) { return static_cast<size_t>(kGateBlocks) * 16 * d; }
+hipError_t launch_route_mfma(const void* X, const void* gate_packed, const float* bias,
+                             bool with_gate, int T, int d, int E, int K, float* scores,
+                             int32_t* topk_ids, float* topk_s, float* sgate, hipStream_t stream);
+hipError_t launch_pack_gate(const void* Wg, const void* w_sg, int d, int E, void* out,
+                            hipStream_t stream);
 hipError_t launch_topk_from_scores(const float* scores, int T, int E, int K, int32_t* topk_ids,
                                    float* topk_s, hipStream_t stream);
 
@@ -43,10 +52,26 @@ hipError_t launch_ffn_f32(bool swiglu, const float* A, int lda, const int32_t* r
                           int ldc, hipStream_t stream);
 
 // ---- ffn_bf16.hip : the same contraction on the matrix cores from packed weights
-hipError_t launch_ffn_bf16_stream(bool swiglu, const void* A, int lda, const int32_t* row_map,
-                                  const void* Bp, size_t group_stride_elems, int Kd, int N,
-                                  const int32_t* tile_info, int64_t max_tiles, int M_dense,
-                                  void* C, int ldc, hipStream_t stream);
+// One group of row tiles: A rows (through row_map when not null) times packed
+// B.  With tile_info null the rows 0..M_dense-1 form one group.  A == nullptr
+// marks an absent group.
+struct StreamGroup {
+    const void* A = nullptr;
+    int lda = 0;
+    const int32_t* row_map = nullptr;
+    const void* Bp = nullptr;
+    size_t group_stride = 0;   // elements between consecutive experts in Bp
+    int Kd = 0, N = 0;
+    const int32_t* tile_info = nullptr;
+    int64_t max_tiles = 0;
+    int M_dense = 0;
+    void* C = nullptr;
+    int ldc = 0;
+    int64_t n_wg = 0;          // filled by the launcher
+};
+// routed experts' tiles and the shared expert's tiles in one launch
+hipError_t launch_ffn_bf16_stream(bool swiglu, StreamGroup routed, StreamGroup shared,
+                                  hipStream_t stream);
 
 // ---- pack.hip : row-major [G][Kd][N] bf16 -> MFMA fragment order
 hipError_t launch_pack_b(const void* W, int G, int Kd, int N, void* out,

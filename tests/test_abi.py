@@ -80,4 +80,5 @@ def test_null_and_workspace_errors_without_launch():
     # packing is bf16-only
     n = ctypes.c_size_t(0)
     assert lib.allocmoe_packed_bytes(ctypes.byref(desc), ctypes.byref(n)) == B.EINVAL
-    assert B.allocmoe_packed_bytes(good(dtype="bf16", d=128, I=256)) == 256 * ((8 * 3 * 128 * 256 * 2 + 255) // 256)
+    assert B.allocmoe_packed_bytes(good(dtype="bf16", d=128, I=256)) == \
+        256 * (((8 * 3 * 128 * 256 + 5 * 16 * 128) * 2 + 255) // 256)
