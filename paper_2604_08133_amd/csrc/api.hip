@@ -299,12 +299,20 @@ allocmoe_status forward_impl(const allocmoe_layer_desc* desc, const void* X,
                                   desc->shared_gate ? w->w_sg : nullptr, T, d, E, K, scores,
                                   topk_ids, topk_s, sgate, stream));
     }
+    // Kernel choice for step 5 (bf16): experts that see tens of rows or more use
+    // the LDS-tiled kernel (128-row tiles), otherwise the weight-streaming kernel
+    // (32-row tiles); decided per group from the descriptor alone.
+    const bool tiled_shapes = bf16 && d % 256 == 0 && I % 128 == 0 && Is % 128 == 0;
+    const bool routed_tiled = tiled_shapes && B >= 24 * static_cast<int64_t>(E);
+    const bool shared_tiled = tiled_shapes && T >= 128;
+    const int bm = routed_tiled ? kTileRowsLarge : kTileRowsSmall;
+    const int64_t max_tiles = max_tiles_for(desc, bm);
     // steps 3-4: Alloc-T selection, dispatch, tile map
     ALLOCMOE_MARK(ALLOCMOE_STAGE_PLAN);
     ALLOCMOE_TRY(launch_plan(topk_s, topk_ids, T, K, desc->K_base, B, E, keep_count,
                              expert_offsets, row_token, row_rank, inv_row,
-                             at<uint64_t>(scr, s.words), at<int32_t>(scr, s.prefix),
-                             kTileRowsSmall, tile_info, stream));
+                             at<uint64_t>(scr, s.words), at<int32_t>(scr, s.prefix), bm, tile_info,
+                             stream));
     // step 5: expert networks over the selected rows, then the shared expert
     if (bf16) {
         const PackedLayout p = packed_of(desc);
@@ -315,9 +323,9 @@ allocmoe_status forward_impl(const allocmoe_layer_desc* desc, const void* X,
         if (B > 0) {
             r1.A = X; r1.lda = d; r1.row_map = row_token; r1.Bp = pk + p.p13;
             r1.group_stride = 2 * dd * II; r1.Kd = d; r1.N = I; r1.tile_info = tile_info;
-            r1.max_tiles = s.max_tiles; r1.C = H; r1.ldc = I;
+            r1.max_tiles = max_tiles; r1.C = H; r1.ldc = I;
             r2.A = H; r2.lda = I; r2.Bp = pk + p.p2; r2.group_stride = II * dd; r2.Kd = I;
-            r2.N = d; r2.tile_info = tile_info; r2.max_tiles = s.max_tiles; r2.C = O; r2.ldc = d;
+            r2.N = d; r2.tile_info = tile_info; r2.max_tiles = max_tiles; r2.C = O; r2.ldc = d;
         }
         if (Is) {
             s1.A = X; s1.lda = d; s1.Bp = pk + p.ps13; s1.group_stride = 2 * dd * SS; s1.Kd = d;
@@ -325,10 +333,22 @@ allocmoe_status forward_impl(const allocmoe_layer_desc* desc, const void* X,
             s2.A = Hs; s2.lda = Is; s2.Bp = pk + p.ps2; s2.group_stride = SS * dd; s2.Kd = Is;
             s2.N = d; s2.M_dense = T; s2.C = Os; s2.ldc = d;
         }
-        ALLOCMOE_MARK(ALLOCMOE_STAGE_FFN1);
-        ALLOCMOE_TRY(launch_ffn_bf16_stream(true, r1, s1, stream));
-        ALLOCMOE_MARK(ALLOCMOE_STAGE_FFN2);
-        ALLOCMOE_TRY(launch_ffn_bf16_stream(false, r2, s2, stream));
+        const StreamGroup none;
+        for (int half = 0; half < 2; ++half) {
+            const bool swiglu = half == 0;
+            const StreamGroup& r = swiglu ? r1 : r2;
+            const StreamGroup& sh = swiglu ? s1 : s2;
+            ALLOCMOE_MARK(swiglu ? ALLOCMOE_STAGE_FFN1 : ALLOCMOE_STAGE_FFN2);
+            if (routed_tiled == shared_tiled) {   // one launch covers both groups
+                ALLOCMOE_TRY(routed_tiled ? launch_ffn_bf16_tiled(swiglu, r, sh, stream)
+                                          : launch_ffn_bf16_stream(swiglu, r, sh, stream));
+            } else {
+                ALLOCMOE_TRY(routed_tiled ? launch_ffn_bf16_tiled(swiglu, r, none, stream)
+                                          : launch_ffn_bf16_stream(swiglu, r, none, stream));
+                ALLOCMOE_TRY(shared_tiled ? launch_ffn_bf16_tiled(swiglu, sh, none, stream)
+                                          : launch_ffn_bf16_stream(swiglu, sh, none, stream));
+            }
+        }
     } else {
         const float* Xf = static_cast<const float*>(X);
         ALLOCMOE_MARK(ALLOCMOE_STAGE_FFN1);

@@ -73,6 +73,12 @@ struct StreamGroup {
 hipError_t launch_ffn_bf16_stream(bool swiglu, StreamGroup routed, StreamGroup shared,
                                   hipStream_t stream);
 
+// Tiled variant (rows-per-tile kTileRowsLarge): needs Kd % 32 == 0 and N % 128 == 0
+// (swiglu) or N % 256 == 0 (plain).
+constexpr int kTileRowsLarge = 128;
+hipError_t launch_ffn_bf16_tiled(bool swiglu, StreamGroup routed, StreamGroup shared,
+                                 hipStream_t stream);
+
 // ---- pack.hip : row-major [G][Kd][N] bf16 -> MFMA fragment order
 hipError_t launch_pack_b(const void* W, int G, int Kd, int N, void* out,
                          size_t group_stride_elems, size_t nblock_stride_elems,

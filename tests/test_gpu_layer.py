@@ -83,6 +83,19 @@ def test_bf16_no_shared_expert():
     check_layer(w, synth.make_layer(w, seed=33))
 
 
+@pytest.mark.parametrize("T,E,K,budget,Kb,I,Ish,bias", [
+    (300, 8, 3, 500, 1, 128, 128, "normal"),    # routed + shared on the tiled kernel, partial tiles
+    (700, 4, 2, 1000, 1, 256, 256, "zipf"),     # several 128-row tiles per expert, skewed
+    (100, 4, 3, 200, 1, 128, 128, "none"),      # routed tiled, shared on the streaming kernel
+    (200, 64, 2, 300, 1, 128, 256, "normal"),   # routed streaming, shared tiled
+    (513, 6, 4, 2052, 0, 384, 0, "zipf"),       # full budget, no shared expert, K_base = 0
+])
+def test_bf16_tiled_kernel_paths(T, E, K, budget, Kb, I, Ish, bias):
+    w = synth.Workload("tiled_bf16", T=T, d=256, E=E, I=I, K=K, K_base=Kb, budget=budget,
+                       dtype="bf16", I_shared=Ish, I_shared_each=Ish, bias_kind=bias)
+    check_layer(w, synth.make_layer(w, seed=51))
+
+
 # ------------------------------------------------- the paper-shaped workloads
 
 def test_deepseek_decode_full():
