@@ -75,7 +75,7 @@ hipError_t launch_ffn_bf16_stream(bool swiglu, StreamGroup routed, StreamGroup s
 
 // Tiled variant (rows-per-tile kTileRowsLarge): needs Kd % 32 == 0 and N % 128 == 0
 // (swiglu) or N % 256 == 0 (plain).
-constexpr int kTileRowsLarge = 128;
+constexpr int kTileRowsLarge = 256;
 hipError_t launch_ffn_bf16_tiled(bool swiglu, StreamGroup routed, StreamGroup shared,
                                  hipStream_t stream);
 
