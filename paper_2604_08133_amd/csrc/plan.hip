@@ -43,6 +43,7 @@ struct PlanShared {
 
 // Exclusive block-wide prefix sum of one value per thread, in thread order.
 // Returns the exclusive prefix; *total (optional) receives the block sum.
+template <int NW = kPlanWaves>
 __device__ __forceinline__ uint32_t block_scan_excl(uint32_t v, uint32_t* wave_tot,
                                                     uint32_t* total) {
     const int lane = lane_id(), wave = threadIdx.x / kWave;
@@ -50,7 +51,7 @@ __device__ __forceinline__ uint32_t block_scan_excl(uint32_t v, uint32_t* wave_t
     if (lane == kWave - 1) wave_tot[wave] = incl;
     __syncthreads();
     uint32_t base = 0, sum = 0;
-    for (int w = 0; w < kPlanWaves; ++w) {
+    for (int w = 0; w < NW; ++w) {
         const uint32_t x = wave_tot[w];
         if (w < wave) base += x;
         sum += x;
@@ -285,6 +286,299 @@ __device__ void tilemap_phase(PlanShared& sh, int E, int bm, int32_t* __restrict
     }
 }
 
+// ---------------------------------------------------------------------------
+// Fast path (T <= 8192 and at most 48 pool keys per thread): the same two
+// phases, but the pool keys are read from global memory once and stay in
+// registers for every pass, and the keep counts, ballot words and prefixes live
+// in LDS, so no phase waits on a global round trip of its own.
+//
+// Selection: thread i owns the contiguous slice [i*C, (i+1)*C) of the pool in
+// (token, rank) order, so "equal keys that precede" is a block-wide exclusive
+// scan of per-thread counts plus a walk through the thread's own keys.
+// Dispatch: the 64 x 64 bit matrix "token t of the batch keeps expert e" is
+// transposed with a 6-stage butterfly of lane exchanges instead of 64 ballots.
+constexpr int kFastMaxT = 8192;
+constexpr int kFastMaxKeys = 48;
+constexpr int kMaxK = 16;          // candidates per token the interface allows
+
+struct FastShared {
+    uint32_t hist[kBins];
+    uint32_t wave_tot[kPlanWaves];
+    uint32_t red_lo[kPlanWaves];
+    uint32_t red_hi[kPlanWaves];
+    uint32_t pick_bin, pick_rank, pick_count;
+    int32_t expert_off[kWave + 1];
+    int32_t seg_tot[kPlanWaves][kWave];
+    int32_t cnt[kFastMaxT];        // keep_count
+    uint64_t words[kFastMaxT];     // [batch][expert]
+    int32_t prefix[kFastMaxT];     // [batch][expert]
+};
+
+// Transpose of a 64 x 64 bit matrix held one row per lane: afterwards lane e
+// holds column e (bit t = former bit e of lane t).
+__device__ __forceinline__ uint64_t wave_transpose64(uint64_t x) {
+    const int lane = lane_id();
+#pragma unroll
+    for (int s = 32; s >= 1; s >>= 1) {
+        // bits whose index has bit `s` clear
+        const uint64_t m = s == 32   ? 0x00000000FFFFFFFFull
+                           : s == 16 ? 0x0000FFFF0000FFFFull
+                           : s == 8  ? 0x00FF00FF00FF00FFull
+                           : s == 4  ? 0x0F0F0F0F0F0F0F0Full
+                           : s == 2  ? 0x3333333333333333ull
+                                     : 0x5555555555555555ull;
+        const uint64_t y = __shfl_xor(x, s, kWave);
+        x = (lane & s) ? ((x & ~m) | ((y & ~m) >> s)) : ((x & m) | ((y & m) << s));
+    }
+    return x;
+}
+
+template <bool SELECT, bool DISPATCH, int NT>
+__global__ __launch_bounds__(NT) void plan_fast_kernel(
+    const float* topk_s, const int32_t* topk_ids, int T, int K, int Kb, int64_t B, int E,
+    int32_t* keep_count, int32_t* expert_offsets, int32_t* row_token, int32_t* row_rank,
+    int32_t* inv_row, int bm, int32_t* tile_info) {
+    __shared__ FastShared sh;
+    constexpr int NW = NT / kWave;            // waves
+    constexpr int NBINS = 2 * NT;             // histogram bins: two per thread
+    constexpr int NBINS_LOG2 = NT == 1024 ? 11 : 9;
+    static_assert(NT == 1024 || NT == 256, "two block sizes");
+    const int tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
+
+    if (SELECT) {
+        const int P = K - Kb;
+        const int n_pool = T * P;
+        const int64_t want = B - static_cast<int64_t>(T) * Kb;
+        if (want <= 0 || want >= n_pool) {
+            const int c = want <= 0 ? Kb : K;
+            for (int t = tid; t < T; t += NT) sh.cnt[t] = c;
+        } else {
+            for (int t = tid; t < T; t += NT) sh.cnt[t] = Kb;
+            // ---- this thread's slice of the pool, in (token, rank) order
+            const int C = (n_pool + NT - 1) / NT;   // <= kFastMaxKeys
+            const int n0 = min(n_pool, tid * C), n_mine = min(n_pool, n0 + C) - n0;
+            const int t_first = n0 / P, j_first = n0 % P;
+            uint32_t key[kFastMaxKeys];
+            {
+                int t = t_first, j = j_first;
+#pragma unroll
+                for (int q = 0; q < kFastMaxKeys; ++q) {
+                    key[q] = 0;
+                    if (q < n_mine) {
+                        key[q] = ordered_key(topk_s[static_cast<size_t>(t) * K + Kb + j]);
+                        if (++j == P) { j = 0; ++t; }
+                    }
+                }
+            }
+            // ---- range of the keys
+            uint32_t lo = 0xFFFFFFFFu, hi = 0u;
+#pragma unroll
+            for (int q = 0; q < kFastMaxKeys; ++q) {
+                if (q >= C) continue;
+                if (q < n_mine) {
+                    lo = min(lo, key[q]);
+                    hi = max(hi, key[q]);
+                }
+            }
+            lo = wave_min_u32(lo);
+            hi = wave_max_u32(hi);
+            if (lane == 0) {
+                sh.red_lo[wave] = lo;
+                sh.red_hi[wave] = hi;
+            }
+            if (tid == 0) {
+                sh.pick_bin = 0;
+                sh.pick_rank = 1;
+                sh.pick_count = 1;
+            }
+            __syncthreads();
+            lo = 0xFFFFFFFFu;
+            hi = 0u;
+            for (int w = 0; w < NW; ++w) {
+                lo = min(lo, sh.red_lo[w]);
+                hi = max(hi, sh.red_hi[w]);
+            }
+            // ---- narrowing passes (see select_phase)
+            uint32_t r = static_cast<uint32_t>(want);
+            uint32_t in_range = static_cast<uint32_t>(n_pool);
+            while (lo < hi) {
+                const uint32_t width_m1 = hi - lo;
+                const int bits = 32 - __builtin_clz(width_m1);
+                const int shift = bits > NBINS_LOG2 ? bits - NBINS_LOG2 : 0;
+                for (int b = tid; b < NBINS; b += NT) sh.hist[b] = 0;
+                __syncthreads();
+#pragma unroll
+                for (int q = 0; q < kFastMaxKeys; ++q) {
+                    if (q >= C) continue;
+                    if (q < n_mine && key[q] >= lo && key[q] <= hi)
+                        atomicAdd(&sh.hist[(key[q] - lo) >> shift], 1u);
+                }
+                __syncthreads();
+                const int b_first = NBINS - 1 - 2 * tid, b_second = b_first - 1;
+                const uint32_t c_first = sh.hist[b_first], c_second = sh.hist[b_second];
+                const uint32_t above = block_scan_excl<NW>(c_first + c_second, sh.wave_tot, nullptr);
+                if (above < r && r <= above + c_first) {
+                    sh.pick_bin = b_first;
+                    sh.pick_rank = r - above;
+                    sh.pick_count = c_first;
+                } else if (above + c_first < r && r <= above + c_first + c_second) {
+                    sh.pick_bin = b_second;
+                    sh.pick_rank = r - above - c_first;
+                    sh.pick_count = c_second;
+                }
+                __syncthreads();
+                const uint32_t pb = sh.pick_bin;
+                r = sh.pick_rank;
+                in_range = sh.pick_count;
+                const uint32_t new_lo = lo + (pb << shift);
+                const uint32_t span_m1 = (shift == 0) ? 0u : ((1u << shift) - 1u);
+                hi = (hi - new_lo < span_m1) ? hi : new_lo + span_m1;
+                lo = new_lo;
+                __syncthreads();
+            }
+            const uint32_t vstar = lo, n_equal = in_range, R = r;
+            // ---- equal keys that precede this thread's slice (only if a tie is split)
+            uint32_t before = 0;
+            if (R != n_equal) {   // uniform
+                uint32_t eq = 0;
+#pragma unroll
+                for (int q = 0; q < kFastMaxKeys; ++q) {
+                    if (q >= C) continue;
+                    if (q < n_mine) eq += key[q] == vstar ? 1u : 0u;
+                }
+                before = block_scan_excl<NW>(eq, sh.wave_tot, nullptr);
+            }
+            // ---- kept entries per token (a token's slice may straddle two threads:
+            // integer adds in LDS, order-independent)
+            {
+                int t = t_first, j = j_first, run = 0;
+#pragma unroll
+                for (int q = 0; q < kFastMaxKeys; ++q) {
+                    if (q >= C) continue;
+                    if (q < n_mine) {
+                        bool keep = key[q] > vstar;
+                        if (key[q] == vstar) {
+                            keep = R == n_equal || before < R;
+                            ++before;
+                        }
+                        run += keep ? 1 : 0;
+                        if (++j == P || q == n_mine - 1) {
+                            if (run) atomicAdd(&sh.cnt[t], run);
+                            run = 0;
+                            j = 0;
+                            ++t;
+                        }
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        for (int t = tid; t < T; t += NT) keep_count[t] = sh.cnt[t];
+    } else {
+        for (int t = tid; t < T; t += NT) sh.cnt[t] = keep_count[t];
+        __syncthreads();
+    }
+    if (!DISPATCH) return;
+
+    const int n_batch = (T + kWave - 1) / kWave;
+    // ---- A: ballot words by bit-matrix transpose (lane e ends up with expert e's word)
+    for (int b = wave; b < n_batch; b += NW) {
+        const int t = b * kWave + lane;
+        uint64_t mine = 0;
+        if (t < T) {
+            const int kt = min(K, sh.cnt[t]);
+            int ids[kMaxK];   // all loads first, so that they are in flight together
+#pragma unroll
+            for (int j = 0; j < kMaxK; ++j)
+                ids[j] = j < K ? topk_ids[static_cast<size_t>(t) * K + j] : 0;
+#pragma unroll
+            for (int j = 0; j < kMaxK; ++j)
+                if (j < kt) mine |= 1ull << (ids[j] & (kWave - 1));
+        }
+        sh.words[b * kWave + lane] = wave_transpose64(mine);
+    }
+    __syncthreads();
+    // ---- B: per expert, exclusive prefix over batches; offsets over experts
+    {
+        const int e = tid % kWave, seg = tid / kWave;
+        const int per_seg = (n_batch + NW - 1) / NW;
+        const int b0 = min(n_batch, seg * per_seg), b1 = min(n_batch, b0 + per_seg);
+        int local = 0;
+        for (int b = b0; b < b1; ++b) local += __popcll(sh.words[b * kWave + e]);
+        sh.seg_tot[seg][e] = local;
+        __syncthreads();
+        int base = 0, total = 0;
+        for (int s2 = 0; s2 < NW; ++s2) {
+            const int v = sh.seg_tot[s2][e];
+            if (s2 < seg) base += v;
+            total += v;
+        }
+        int run = base;
+        for (int b = b0; b < b1; ++b) {
+            sh.prefix[b * kWave + e] = run;
+            run += __popcll(sh.words[b * kWave + e]);
+        }
+        if (seg == 0) {
+            const int incl = wave_scan_incl(e < E ? total : 0);
+            sh.expert_off[e + 1] = incl;
+            if (e == 0) sh.expert_off[0] = 0;
+        }
+        __syncthreads();
+        if (tid <= E) expert_offsets[tid] = sh.expert_off[tid];
+    }
+    // ---- C: place every pair
+    for (int b = wave; b < n_batch; b += NW) {
+        const int t = b * kWave + lane;
+        if (t >= T) continue;
+        const int kt = min(K, sh.cnt[t]);
+        const uint64_t below = lanemask_lt();
+        int ids[kMaxK];
+#pragma unroll
+        for (int j = 0; j < kMaxK; ++j) ids[j] = j < K ? topk_ids[static_cast<size_t>(t) * K + j] : 0;
+#pragma unroll
+        for (int j = 0; j < kMaxK; ++j) {
+            if (j >= K) continue;
+            int row = -1;
+            if (j < kt) {
+                const int e = ids[j] & (kWave - 1);
+                const int idx = b * kWave + e;
+                row = sh.expert_off[e] + sh.prefix[idx] + __popcll(sh.words[idx] & below);
+                if (row < B) {   // holds whenever sum_t keep_count[t] <= budget
+                    row_token[row] = t;
+                    row_rank[row] = j;
+                }
+            }
+            inv_row[static_cast<size_t>(t) * K + j] = row;
+        }
+    }
+    // ---- tile map
+    if (tile_info != nullptr && tid < kWave) {
+        const int e = tid;
+        const int rows = e < E ? sh.expert_off[e + 1] - sh.expert_off[e] : 0;
+        const int nt = (rows + bm - 1) / bm;
+        const int incl = wave_scan_incl(nt);
+        const int first = incl - nt;
+        for (int i = 0; i < nt; ++i) {
+            int32_t* ent = tile_info + 4 + 4 * static_cast<size_t>(first + i);
+            ent[0] = e;
+            ent[1] = sh.expert_off[e] + i * bm;
+            ent[2] = min(bm, rows - i * bm);
+            ent[3] = 0;
+        }
+        if (e == kWave - 1) tile_info[0] = incl;
+    }
+}
+
+// 0: large sizes (generic kernels), 256 / 1024: block size of the fast kernel.
+// Small problems run on 4 waves (one per SIMD): the kernel is a chain of short
+// dependent phases, and fewer waves means each instruction issues sooner.
+inline int fast_path_threads(int T, int K, int Kb) {
+    const int64_t n_pool = static_cast<int64_t>(T) * (K - Kb);
+    if (T > kFastMaxT) return 0;
+    if (T <= 1024 && (n_pool + 255) / 256 <= kFastMaxKeys) return 256;
+    return (n_pool + kPlanThreads - 1) / kPlanThreads <= kFastMaxKeys ? kPlanThreads : 0;
+}
+
 __global__ __launch_bounds__(kPlanThreads) void select_kernel(const float* topk_s, int T, int K,
                                                               int Kb, int64_t B,
                                                               int32_t* keep_count) {
@@ -317,8 +611,18 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
 
 hipError_t launch_select(const float* topk_s, int T, int K, int Kb, int64_t B,
                          int32_t* keep_count, hipStream_t stream) {
-    hipLaunchKernelGGL(select_kernel, dim3(1), dim3(kPlanThreads), 0, stream, topk_s, T, K, Kb, B,
-                       keep_count);
+    const int nt = fast_path_threads(T, K, Kb);
+    if (nt == 256)
+        hipLaunchKernelGGL((plan_fast_kernel<true, false, 256>), dim3(1), dim3(256), 0, stream,
+                           topk_s, nullptr, T, K, Kb, B, 0, keep_count, nullptr, nullptr, nullptr,
+                           nullptr, 0, nullptr);
+    else if (nt == 1024)
+        hipLaunchKernelGGL((plan_fast_kernel<true, false, 1024>), dim3(1), dim3(1024), 0, stream,
+                           topk_s, nullptr, T, K, Kb, B, 0, keep_count, nullptr, nullptr, nullptr,
+                           nullptr, 0, nullptr);
+    else
+        hipLaunchKernelGGL(select_kernel, dim3(1), dim3(kPlanThreads), 0, stream, topk_s, T, K, Kb,
+                           B, keep_count);
     return hipGetLastError();
 }
 
@@ -326,9 +630,19 @@ hipError_t launch_dispatch(const int32_t* topk_ids, const int32_t* keep_count, i
                            int E, int64_t B, int32_t* expert_offsets, int32_t* row_token,
                            int32_t* row_rank, int32_t* inv_row, uint64_t* words, int32_t* prefix,
                            int bm, int32_t* tile_info, hipStream_t stream) {
-    hipLaunchKernelGGL(dispatch_kernel, dim3(1), dim3(kPlanThreads), 0, stream, topk_ids,
-                       keep_count, T, K, E, B, expert_offsets, row_token, row_rank, inv_row,
-                       words, prefix, bm, tile_info);
+    const int nt = fast_path_threads(T, K, K);
+    if (nt == 256)
+        hipLaunchKernelGGL((plan_fast_kernel<false, true, 256>), dim3(1), dim3(256), 0, stream,
+                           nullptr, topk_ids, T, K, 0, B, E, const_cast<int32_t*>(keep_count),
+                           expert_offsets, row_token, row_rank, inv_row, bm, tile_info);
+    else if (nt == 1024)
+        hipLaunchKernelGGL((plan_fast_kernel<false, true, 1024>), dim3(1), dim3(1024), 0, stream,
+                           nullptr, topk_ids, T, K, 0, B, E, const_cast<int32_t*>(keep_count),
+                           expert_offsets, row_token, row_rank, inv_row, bm, tile_info);
+    else
+        hipLaunchKernelGGL(dispatch_kernel, dim3(1), dim3(kPlanThreads), 0, stream, topk_ids,
+                           keep_count, T, K, E, B, expert_offsets, row_token, row_rank, inv_row,
+                           words, prefix, bm, tile_info);
     return hipGetLastError();
 }
 
@@ -336,9 +650,19 @@ hipError_t launch_plan(const float* topk_s, const int32_t* topk_ids, int T, int 
                        int64_t B, int E, int32_t* keep_count, int32_t* expert_offsets,
                        int32_t* row_token, int32_t* row_rank, int32_t* inv_row, uint64_t* words,
                        int32_t* prefix, int bm, int32_t* tile_info, hipStream_t stream) {
-    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, stream, topk_s, topk_ids, T,
-                       K, Kb, B, E, keep_count, expert_offsets, row_token, row_rank, inv_row,
-                       words, prefix, bm, tile_info);
+    const int nt = fast_path_threads(T, K, Kb);
+    if (nt == 256)
+        hipLaunchKernelGGL((plan_fast_kernel<true, true, 256>), dim3(1), dim3(256), 0, stream,
+                           topk_s, topk_ids, T, K, Kb, B, E, keep_count, expert_offsets, row_token,
+                           row_rank, inv_row, bm, tile_info);
+    else if (nt == 1024)
+        hipLaunchKernelGGL((plan_fast_kernel<true, true, 1024>), dim3(1), dim3(1024), 0, stream,
+                           topk_s, topk_ids, T, K, Kb, B, E, keep_count, expert_offsets, row_token,
+                           row_rank, inv_row, bm, tile_info);
+    else
+        hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, stream, topk_s, topk_ids,
+                           T, K, Kb, B, E, keep_count, expert_offsets, row_token, row_rank,
+                           inv_row, words, prefix, bm, tile_info);
     return hipGetLastError();
 }
 

@@ -52,7 +52,8 @@ def budgets_for(T, K, Kb):
 
 
 @pytest.mark.parametrize("T,E,K", [(64, 8, 2), (32, 64, 6), (1, 64, 6), (63, 17, 5), (333, 60, 4),
-                                   (1000, 64, 6), (1025, 64, 8), (4096, 64, 6), (8192, 64, 6)])
+                                   (1000, 64, 6), (1025, 64, 8), (4096, 64, 6), (8192, 64, 6),
+                                   (8192, 64, 8), (9000, 64, 6)])   # the last two: the large-size code path
 @pytest.mark.parametrize("Kb", [0, 1, 2])
 def test_bit_exact_distinct_scores(T, E, K, Kb):
     if Kb > K:
@@ -66,7 +67,7 @@ def test_bit_exact_distinct_scores(T, E, K, Kb):
 
 @pytest.mark.parametrize("levels", [4, 64, 1024])
 @pytest.mark.parametrize("T,E,K,Kb", [(200, 16, 4, 1), (3000, 64, 6, 1), (3000, 64, 6, 0),
-                                      (2049, 60, 4, 2)])
+                                      (2049, 60, 4, 2), (8192, 64, 6, 1), (9500, 64, 6, 1)])
 def test_bit_exact_with_ties(levels, T, E, K, Kb):
     scores = synth.make_scores(T, E, seed=levels + T, quantize_levels=levels)
     for budget in budgets_for(T, K, Kb) + [T * Kb + T // 3]:
