@@ -33,6 +33,7 @@ def parse_args():
                    choices=["decode", "prefill", "qwen", "stack"])
     p.add_argument("--budget-ratio", type=float, default=0.5,
                    help="layer budget as a fraction of T*K (the metric is quoted at 0.5)")
+    p.add_argument("--layers", type=int, default=26, help="layers of the stack workload")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--copy-probe", action="store_true",
                    help="only run a plain device copy of 1 GiB (calibrates the rocprofv3 "
@@ -135,20 +136,28 @@ def main():
         return
 
     w = workload_for(args.workload, args.budget_ratio)
-    on_cpu = w.T * w.d <= (1 << 24) and args.workload in ("decode",)
+    on_cpu = args.workload == "decode"
     # Inputs: generated on the CPU for the small workload (the oracle baseline
-    # needs the same bytes), on the GPU for the big ones.
+    # needs the same bytes), on the GPU for the big ones.  The stack workload is
+    # `--layers` independent layers (own weights, own input, own budget: layers of
+    # a model interact only through the budgets Alloc-L gives them).
     layer_cpu = synth.make_layer(w, device="cpu") if on_cpu else None
-    if layer_cpu is not None:
-        dev = DeviceLayer(w, layer_cpu)
+    if args.workload == "stack":
+        budgets = synth.stack_budgets(args.layers, w.T, w.K, w.K_base, args.budget_ratio)
+        works = [w.with_(budget=b) for b in budgets]
+        devs = [DeviceLayer(wl, synth.make_layer(wl, layer=i, device="cuda"))
+                for i, wl in enumerate(works)]
     else:
-        dev = DeviceLayer(w, synth.make_layer(w, device="cuda"))
-    desc = dev.desc()
-    ws = dev.workspace(desc)
-    Y = torch.empty((w.T, w.d), dtype=dev.dtype, device=dev.device)
+        works = [w]
+        devs = [DeviceLayer(w, layer_cpu if on_cpu else synth.make_layer(w, device="cuda"))]
+    descs = [dv.desc() for dv in devs]
+    ws = torch.empty(max(B.allocmoe_workspace_bytes(dc) for dc in descs), dtype=torch.uint8,
+                     device="cuda")
+    Y = torch.empty((w.T, w.d), dtype=devs[0].dtype, device="cuda")
 
     def step():
-        B.allocmoe_moe_forward(desc, dev.X, dev.weights, Y, ws)
+        for dv, dc in zip(devs, descs):
+            B.allocmoe_moe_forward(dc, dv.X, dv.weights, Y, ws)
 
     for _ in range(args.warmup):
         step()
@@ -161,55 +170,62 @@ def main():
     ms_per_step = 1e3 * elapsed / args.steps
 
     # per-kernel durations: the same steps again through the event-instrumented
-    # entry point (HIP events recorded by the library on the launch stream)
+    # entry point (HIP events recorded by the library on the launch stream);
+    # along the way, read back how many experts each layer activated
     stage_ms = [0.0] * len(B.STAGES)
-    for _ in range(args.steps):
-        ms = B.allocmoe_moe_forward_timed(desc, dev.X, dev.weights, Y, ws)
-        stage_ms = [a + b for a, b in zip(stage_ms, ms)]
+    n_active_sum, pairs_sum = 0, 0
+    for it in range(args.steps):
+        for dv, dc, wl in zip(devs, descs, works):
+            ms = B.allocmoe_moe_forward_timed(dc, dv.X, dv.weights, Y, ws)
+            stage_ms = [a + b for a, b in zip(stage_ms, ms)]
+            if it == 0:
+                L = B.allocmoe_workspace_layout(dc)
+                offs = B.ws_view(ws, L.expert_offsets, (wl.E + 1,), torch.int32).cpu()
+                n_active_sum += int(((offs[1:] - offs[:-1]) > 0).sum())
+                assert int(offs[-1]) == wl.budget, "selected pairs != layer budget"
+                pairs_sum += int(offs[-1])
     stage_ms = [v / args.steps for v in stage_ms]
     stages = dict(zip(B.STAGES, stage_ms))
+    nL = len(devs)
 
-    mid = dev.intermediates()
-    offs = mid["expert_offsets"].cpu()
-    rows_per_expert = (offs[1:] - offs[:-1])
-    n_active = int((rows_per_expert > 0).sum())
-    Bn = int(offs[-1])
-    assert Bn == w.budget, "selected pairs != layer budget"
-
-    # ---- roofline of the dominant kernel
+    # ---- roofline of the dominant kernel (summed over the layers of a step)
     d, I, Is, T = w.d, w.I, w.I_shared, w.T
     # ffn1 launch = routed rows + shared expert: W1,W3 once per active expert and
     # once for the shared expert; x rows in, H rows out
-    ffn1_bytes = (n_active * 2 * d * I * 2 + Bn * (d * 2 + I * 2)
-                  + (2 * d * Is * 2 + T * (d * 2 + Is * 2) if Is else 0))
-    ffn1_flops = Bn * 2 * d * (2 * I) + T * 2 * d * (2 * Is)
+    ffn1_bytes = (n_active_sum * 2 * d * I * 2 + pairs_sum * (d * 2 + I * 2)
+                  + nL * (2 * d * Is * 2 + T * (d * 2 + Is * 2) if Is else 0))
+    ffn1_flops = pairs_sum * 2 * d * (2 * I) + nL * T * 2 * d * (2 * Is)
     dom = "ffn1"
     dom_ms = stages[dom]
-    kernel_name = "ffn_bf16_stream_kernel<true>"
     if args.workload == "decode":
+        kernel_name = "ffn_bf16_stream_kernel<true>"
         roof = {"bound": "hbm", "achieved": ffn1_bytes / (dom_ms * 1e-3) / 1e9,
                 "peak": HBM_PEAK_GBS, "unit": "GB/s"}
     else:
+        kernel_name = "ffn_bf16_tiled_kernel<true>"
         roof = {"bound": "mfma", "achieved": ffn1_flops / (dom_ms * 1e-3) / 1e12,
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s"}
+        # what the roofline allows at this arithmetic intensity: min(peak, flop/byte x HBM)
+        roof["attainable"] = min(MFMA_BF16_PEAK_TFLOPS, ffn1_flops / ffn1_bytes * HBM_PEAK_GBS / 1e3)
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["traffic"] = traffic_from_profiles(args.workload, dom)
     roof["kernel"] = kernel_name
-    roof["kernel_ms"] = dom_ms
-    roof["algorithmic_bytes"] = ffn1_bytes
-    roof["algorithmic_flops"] = ffn1_flops
+    roof["kernel_ms"] = dom_ms / nL
+    roof["launches_per_step"] = nL
+    roof["algorithmic_bytes"] = ffn1_bytes / nL
+    roof["algorithmic_flops"] = ffn1_flops / nL
 
     # whole-step algorithmic traffic and work (context for the step time)
-    step_bytes = (n_active * 3 * d * I * 2 + 3 * d * Is * 2          # expert + shared weights
-                  + T * d * 2 * 2 + d * w.E * 2                      # X (gate), Y, Wg
-                  + Bn * (d * 2 + 2 * I * 2 + 2 * d * 4)             # x gather, H w+r, O w+r
-                  + (T * (d * 2 + 2 * Is * 2 + 2 * d * 4) if Is else 0))
-    step_flops = Bn * 6 * d * I + T * 6 * d * Is + T * 2 * d * w.E
+    step_bytes = (n_active_sum * 3 * d * I * 2 + nL * 3 * d * Is * 2   # expert + shared weights
+                  + nL * (T * d * 2 * 2 + d * w.E * 2)                 # X (gate), Y, Wg
+                  + pairs_sum * (d * 2 + 2 * I * 2 + 2 * d * 4)        # x gather, H w+r, O w+r
+                  + (nL * T * (d * 2 + 2 * Is * 2 + 2 * d * 4) if Is else 0))
+    step_flops = pairs_sum * 6 * d * I + nL * (T * 6 * d * Is + T * 2 * d * w.E)
     step_info = {
         "algorithmic_bytes": step_bytes, "algorithmic_flops": step_flops,
         "hbm_frac": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "mfma_frac": step_flops / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-        "active_experts": n_active,
+        "active_experts": n_active_sum, "layers": nL,
         "stage_ms": {k: round(v, 5) for k, v in stages.items()},
     }
 
@@ -221,10 +237,11 @@ def main():
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": w.name, "T": w.T, "d": w.d, "E": w.E, "I": w.I, "K": w.K,
-                   "K_base": w.K_base, "budget": w.budget, "budget_ratio": args.budget_ratio,
-                   "I_shared": w.I_shared, "weights": "re-tiled once by allocmoe_pack_weights, "
-                   "outside the timed region"},
+        "config": {"workload": w.name + (f"_x{nL}_layers" if nL > 1 else ""), "T": w.T, "d": w.d,
+                   "E": w.E, "I": w.I, "K": w.K, "K_base": w.K_base,
+                   "budget": [wl.budget for wl in works] if nL > 1 else w.budget,
+                   "budget_ratio": args.budget_ratio, "I_shared": w.I_shared,
+                   "weights": "re-tiled once by allocmoe_pack_weights, outside the timed region"},
         "roofline": roof,
         "step": step_info,
     }
