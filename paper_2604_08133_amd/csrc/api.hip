@@ -300,8 +300,9 @@ allocmoe_status forward_impl(const allocmoe_layer_desc* desc, const void* X,
                                   topk_ids, topk_s, sgate, stream));
     }
     // Kernel choice for step 5 (bf16): experts that see tens of rows or more use
-    // the LDS-tiled kernel (128-row tiles), otherwise the weight-streaming kernel
-    // (32-row tiles); decided per group from the descriptor alone.
+    // the register-blocked tile kernel (256-row tiles), otherwise the
+    // weight-streaming kernel (32-row tiles); decided per group from the descriptor
+    // alone.
     const bool tiled_shapes = bf16 && d % 256 == 0 && I % 128 == 0 && Is % 128 == 0;
     const bool routed_tiled = tiled_shapes && B >= 24 * static_cast<int64_t>(E);
     const bool shared_tiled = tiled_shapes && T >= 128;
@@ -340,12 +341,12 @@ allocmoe_status forward_impl(const allocmoe_layer_desc* desc, const void* X,
             const StreamGroup& sh = swiglu ? s1 : s2;
             ALLOCMOE_MARK(swiglu ? ALLOCMOE_STAGE_FFN1 : ALLOCMOE_STAGE_FFN2);
             if (routed_tiled == shared_tiled) {   // one launch covers both groups
-                ALLOCMOE_TRY(routed_tiled ? launch_ffn_bf16_tiled(swiglu, r, sh, stream)
+                ALLOCMOE_TRY(routed_tiled ? launch_ffn_bf16_t256(swiglu, r, sh, stream)
                                           : launch_ffn_bf16_stream(swiglu, r, sh, stream));
             } else {
-                ALLOCMOE_TRY(routed_tiled ? launch_ffn_bf16_tiled(swiglu, r, none, stream)
+                ALLOCMOE_TRY(routed_tiled ? launch_ffn_bf16_t256(swiglu, r, none, stream)
                                           : launch_ffn_bf16_stream(swiglu, r, none, stream));
-                ALLOCMOE_TRY(shared_tiled ? launch_ffn_bf16_tiled(swiglu, sh, none, stream)
+                ALLOCMOE_TRY(shared_tiled ? launch_ffn_bf16_t256(swiglu, sh, none, stream)
                                           : launch_ffn_bf16_stream(swiglu, sh, none, stream));
             }
         }

@@ -1,0 +1,361 @@
+// bf16 expert networks on the matrix cores for prefill-shaped layers (Section
+// 3.1: one feed-forward execution per selected pair), fp32 accumulation:
+//   H = silu(A W1) * (A W3)   (SWIGLU, bf16 out)    or    O = A W2   (fp32 out).
+//
+// Register-blocked 256 x 256 tile on 4 waves (one per SIMD, all 512 registers).
+//
+// A workgroup owns <= 256 rows of one expert times 128 SwiGLU columns (128 of
+// W1 and the same 128 of W3) or 256 columns of W2.  Wave w owns 64 of those
+// weight columns (two 32-column MFMA fragments: W1|W3 of the same columns, or
+// two neighbouring W2 blocks) times every 32-row block of the tile: up to
+// 8 x 2 accumulators of 32x32, 256 registers.
+//
+//  * The weights never pass through LDS: they were re-tiled once into MFMA
+//    B-fragment order, a wave is the only consumer of its columns, so each lane
+//    loads its 16 bytes per fragment straight from global memory (1 KB
+//    contiguous per wave-load) into a ring of 8 fragment pairs (8 k16 steps =
+//    128 k ahead of use).
+//  * The activation rows go global -> LDS directly (no VGPR staging) into a ring
+//    of 4 slots of 256 rows x 64 k; lanes 8r..8r+7 fetch the eight 16-byte
+//    chunks of row r (one 128-byte line per row), XOR-swizzled so that every
+//    MFMA A-operand read is one conflict-free ds_read_b128.  Loads run three
+//    slots ahead; one workgroup barrier per 64 k.
+//  * Per 16 k a wave issues 2*NRB MFMAs for NRB LDS reads + 2 global loads, so a
+//    tile with fewer than 256 rows costs in proportion to its 32-row blocks.
+#include <algorithm>
+#include <type_traits>
+
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace allocmoe {
+
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+constexpr int kRows = kTileRowsLarge;   // rows per tile
+constexpr int kStepK = 64;              // contraction elements per ring slot
+constexpr int kSlots = 4;
+constexpr int kWaves = 4;
+constexpr int kSlotBytes = kRows * kStepK * 2;
+constexpr int kXcds = 8;                // accelerator dies (one L2 each) of an MI355X
+constexpr int kBRing = 8;               // k16 steps of weight fragments held in registers
+
+__device__ __forceinline__ int acc_row(int r, int l) { return 8 * (r / 4) + 4 * (l / 32) + (r % 4); }
+
+// 8 rows x 128 B of activations, global -> LDS directly: lane l's 16 bytes land
+// at lds_addr + 16 l (M0 holds the wave-uniform LDS base; one idle state between
+// writing M0 and the load that reads it).  Written as asm, hidden from the
+// compiler's wait-count insertion: it treats a direct-to-LDS load as touching
+// both memory paths and then drains *all* outstanding loads (vmcnt(0)) at the
+// next use of any loaded register, which would serialise the weight prefetch.
+// Hidden, these loads still count in vmcnt, in issue order: every wait the
+// compiler emits for a weight register is then stricter than needed, never
+// weaker, and the waits for the slots themselves are written by hand.
+__device__ __forceinline__ void load_rows_to_lds(const bf16x8* g, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(g), "s"(lds_addr)
+                 : "memory", "m0");
+}
+
+// Workgroup barrier without the memory fence of __syncthreads(): the fence
+// would wait for every outstanding load, i.e. also for the prefetched slots.
+// What a step needs is awaited explicitly (vmcnt) before the barrier.
+__device__ __forceinline__ void wg_barrier_nofence() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt_le() {
+    // s_waitcnt with expcnt/lgkmcnt unconstrained; vmcnt is bits [3:0] and [15:14]
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
+template <bool SWIGLU, int NRB>
+__device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda,
+                                          const int32_t* row_map, const bf16x8* b0,
+                                          const bf16x8* b1, int KT, int wave, int lane, int row0,
+                                          int rows, int nt, void* C, int ldc) {
+    f32x16 acc[NRB][2];
+#pragma unroll
+    for (int i = 0; i < NRB; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = f32x16{0};
+
+    // A: per slot, wave w stages rows 32 i + 8 w .. + 7 of every row block i that
+    // holds real rows (NRB wave-loads): lane 8 r + p fetches the chunk that belongs
+    // at position p of row r.  Rows past the tile's end re-read its last row (in
+    // bounds, never stored).
+    const bf16x8* arow[NRB];
+#pragma unroll
+    for (int i = 0; i < NRB; ++i) {
+        const int R = 32 * i + 8 * wave + lane / 8;
+        const int my_row = row0 + min(R, rows - 1);
+        const long src = row_map ? row_map[my_row] : my_row;
+        arow[i] = reinterpret_cast<const bf16x8*>(A + static_cast<size_t>(src) * lda) +
+                  ((lane % 8) ^ ((R >> 1) & 7));
+    }
+    const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(
+        static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds)) + wave * 1024);
+    auto issue_a = [&](int s, int slot) {
+#pragma unroll
+        for (int i = 0; i < NRB; ++i)
+            load_rows_to_lds(arow[i] + s * (kStepK / 8), lds_wave + slot * kSlotBytes + i * 4096);
+    };
+    const int KQ = 4 * KT;   // k16 steps in total
+    bf16x8 breg[kBRing][2];
+    auto load_b = [&](int q, int r) {
+        breg[r][0] = b0[static_cast<size_t>(q) * kWave];
+        breg[r][1] = b1[static_cast<size_t>(q) * kWave];
+    };
+    // A operand of row block i, k16 chunk kc of a slot: lane l reads row m = l%32 of
+    // the block, 16-byte chunk c = 2 kc + l/32 of that row, stored at position
+    // c ^ ((m/2) % 8) of the row's 128 bytes.
+    const int m = lane % 32, sw = (m >> 1) & 7;
+    int a_off[4];
+#pragma unroll
+    for (int kc = 0; kc < 4; ++kc) a_off[kc] = (m * 8 + ((2 * kc + lane / 32) ^ sw)) * 16;
+    auto read_a = [&](int slot, int kc, bf16x8 (&a)[NRB]) {
+        const char* base = lds + slot * kSlotBytes + a_off[kc];
+#pragma unroll
+        for (int i = 0; i < NRB; ++i) a[i] = *reinterpret_cast<const bf16x8*>(base + i * (32 * 128));
+    };
+    auto multiply = [&](const bf16x8 (&a)[NRB], const bf16x8 (&b)[2]) {
+#pragma unroll
+        for (int i = 0; i < NRB; ++i) {
+            acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[0], acc[i][0], 0, 0, 0);
+            acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[1], acc[i][1], 0, 0, 0);
+        }
+    };
+
+    // Load schedule.  Per k16 step u (8 per loop pass = 2 slots): the step's MFMAs,
+    // then 2 loads refilling its weight registers for step u + 8 (the compiler
+    // inserts the waits for those registers); after the third k16 of a slot
+    // additionally NRB loads refilling the slot used one step ago with the slot
+    // three ahead.  Slot s+1 is awaited after the third k16 of slot s: it was issued
+    // two slots earlier, followed by 2 + (6 + NRB + 2) + 6 loads    -> kWaitA.
+    // The prologue issues slot 0 and then exactly the sequence of one loop pass
+    // (weights of steps 0-2, slot 1, steps 3-6, slot 2, step 7), so that count
+    // holds from the first pass on.  Loads past the end of the contraction re-read
+    // the last step (in bounds, never multiplied), which keeps the count uniform.
+    constexpr int kWaitA = 16 + NRB;
+    issue_a(0, 0);
+#pragma unroll
+    for (int r = 0; r < kBRing; ++r) {
+        load_b(r, r);
+        if (r == 2) issue_a(min(1, KT - 1), 1);
+        if (r == 6) issue_a(min(2, KT - 1), 2);
+    }
+    wait_vmcnt_le<2 * kBRing + 2 * NRB>();   // slot 0 has landed (this wave's part)
+    wg_barrier_nofence();
+    bf16x8 af[2][NRB];
+    read_a(0, 0, af[0]);
+
+    for (int s2 = 0; s2 < KT; s2 += 2) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int s = s2 + u / 4, kc = u % 4;
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_sched_barrier(0);
+            // next step's A fragments are read under the first MFMAs of this step
+            if (kc < 3)
+                read_a(s & 3, kc + 1, af[(u + 1) & 1]);
+            else
+                read_a((s + 1) & 3, 0, af[(u + 1) & 1]);
+            multiply(af[u & 1], breg[u]);
+#pragma unroll
+            for (int i = 0; i < NRB; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, NRB, 0);     // the remaining MFMAs
+            __builtin_amdgcn_sched_barrier(0);
+            load_b(min(4 * s2 + u + kBRing, KQ - 1), u);
+            if (kc == 2) {
+                // this wave's part of the next slot has landed; after the barrier
+                // everybody's has, and everybody is done with the slot before this one
+                wait_vmcnt_le<kWaitA>();
+                wg_barrier_nofence();
+                issue_a(min(s + 3, KT - 1), (s + 3) & 3);
+            }
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    wait_vmcnt_le<0>();   // the surplus loads have landed before registers and LDS are reused
+
+    // epilogue: lane l, register r -> row 8*(r/4) + 4*(l/32) + r%4, column l%32
+    const int col = lane % 32;
+#pragma unroll
+    for (int i = 0; i < NRB; ++i) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int mr = i * 32 + acc_row(r, lane);
+            if (mr >= rows) continue;
+            if (SWIGLU) {
+                const float av = acc[i][0][r], bv = acc[i][1][r];
+                const size_t off = static_cast<size_t>(row0 + mr) * ldc + nt * 128 + wave * 32 + col;
+                static_cast<bf16_t*>(C)[off] = f32_to_bf16((av / (1.f + __expf(-av))) * bv);
+            } else {
+                const size_t off = static_cast<size_t>(row0 + mr) * ldc + nt * 256 + wave * 64 + col;
+                static_cast<float*>(C)[off] = acc[i][0][r];
+                static_cast<float*>(C)[off + 32] = acc[i][1][r];
+            }
+        }
+    }
+}
+
+#ifdef ALLOCMOE_TRACE
+__device__ long long t256_trace[2][1 << 14][4];
+#endif
+
+template <bool SWIGLU>
+__global__ __launch_bounds__(kWaves* kWave, 1) void ffn_bf16_t256_kernel(StreamGroup g0,
+                                                                        StreamGroup g1) {
+    __shared__ __attribute__((aligned(1024))) char lds[kSlots * kSlotBytes];
+
+    // Work order.  Workgroups are dealt to the 8 XCDs round-robin by blockIdx, and
+    // each XCD has its own L2: workgroup i is item i/8 of XCD i%8's list.
+    //  * The dense (shared-expert) group comes first.  The XCDs form an
+    //    xr x (8/xr) grid over its (row tiles, column tiles), interleaved, and an
+    //    XCD's items are ordered (column tile, row tile): the workgroups of the
+    //    first round start together and stay in step, so a weight stream is fetched
+    //    into an L2 once for all the XCD's row tiles, an activation tile once for
+    //    all its column tiles.
+    //  * Then the routed tiles in the tile map's order (longest first), tile t on
+    //    XCD t % 8 with its column tiles back to back (they share the gathered
+    //    activation rows).  The launch ends on the cheapest workgroups.
+    constexpr int kColsPerTile = SWIGLU ? 128 : 256;
+    const int xcd = blockIdx.x % kXcds, idx = blockIdx.x / kXcds;
+    const int nt0 = g0.A ? g0.N / kColsPerTile : 1, nt1 = g1.A ? g1.N / kColsPerTile : 1;
+    int S = 0, s_rows = 1;     // dense group: items and row tiles of this XCD
+    const int xr = g1.xr, xc = kXcds / xr, xri = xcd % xr, xci = xcd / xr;
+    if (g1.A != nullptr) {
+        const int tiles = (g1.M_dense + kRows - 1) / kRows;
+        s_rows = (tiles - xri + xr - 1) / xr;
+        S = s_rows * ((nt1 - xci + xc - 1) / xc);
+    }
+    const bool first = idx >= S;
+    const StreamGroup& g = first ? g0 : g1;
+    int tile, nt;
+    if (first) {
+        if (g0.A == nullptr) return;
+        const int sub = idx - S;
+        const int tiles = g0.tile_info ? g0.tile_info[0] : (g0.M_dense + kRows - 1) / kRows;
+        tile = sub / nt0 * kXcds + xcd;
+        nt = sub % nt0;
+        if (tile >= tiles) return;   // the grid is sized for the host's bound
+    } else {
+        tile = xri + xr * (idx % s_rows);
+        nt = xci + xc * (idx / s_rows);
+    }
+
+    const bf16_t* __restrict__ A = static_cast<const bf16_t*>(g.A);
+    const bf16_t* __restrict__ Bp = static_cast<const bf16_t*>(g.Bp);
+    const int32_t* __restrict__ row_map = g.row_map;
+    const int32_t* __restrict__ tile_info = g.tile_info;
+    const int lda = g.lda, Kd = g.Kd, ldc = g.ldc, M_dense = g.M_dense;
+    int e, row0, rows;
+    if (tile_info != nullptr) {
+        const int32_t* ent = tile_info + kTileHdr + 4 * static_cast<size_t>(tile);
+        e = ent[0];
+        row0 = ent[1];
+        rows = ent[2];
+    } else {
+        e = 0;
+        row0 = tile * kRows;
+        rows = min(kRows, M_dense - row0);
+    }
+    const int lane = lane_id(), wave = threadIdx.x / kWave;
+    const int n_rb = (rows + 31) / 32;   // 32-row blocks that hold real rows
+    const int KT = Kd / kStepK;
+#ifdef ALLOCMOE_TRACE
+    const long long trace_t0 = wall_clock64(), trace_c0 = clock64();
+#endif
+
+    // B: the two fragment streams of this wave's 64 weight columns; a stream is
+    // Kd/16 fragments of 64 lanes x 16 B, contiguous
+    const size_t stream_elems = static_cast<size_t>(Kd) * 32;
+    const size_t sidx = SWIGLU ? static_cast<size_t>(4 * nt + wave) * 2
+                               : static_cast<size_t>(8 * nt + 2 * wave);
+    const bf16x8* b0 = reinterpret_cast<const bf16x8*>(
+                           Bp + static_cast<size_t>(e) * g.group_stride + sidx * stream_elems) + lane;
+    const bf16x8* b1 = b0 + stream_elems / 8;
+
+#define ALLOCMOE_T256_CASE(n) \
+    case n: t256_body<SWIGLU, n>(lds, A, lda, row_map, b0, b1, KT, wave, lane, row0, rows, nt, g.C, ldc); break;
+    switch (n_rb) {   // uniform over the workgroup
+        ALLOCMOE_T256_CASE(1)
+        ALLOCMOE_T256_CASE(2)
+        ALLOCMOE_T256_CASE(3)
+        ALLOCMOE_T256_CASE(4)
+        ALLOCMOE_T256_CASE(5)
+        ALLOCMOE_T256_CASE(6)
+        ALLOCMOE_T256_CASE(7)
+        default: t256_body<SWIGLU, 8>(lds, A, lda, row_map, b0, b1, KT, wave, lane, row0, rows, nt, g.C, ldc); break;
+    }
+#undef ALLOCMOE_T256_CASE
+#ifdef ALLOCMOE_TRACE
+    if (threadIdx.x == 0 && blockIdx.x < (1 << 14)) {
+        long long* t = t256_trace[SWIGLU ? 0 : 1][blockIdx.x];
+        t[0] = trace_t0;
+        t[1] = wall_clock64();
+        t[2] = (first ? 1 : 0) | (n_rb << 4) | (nt << 8) | (tile << 16) | ((clock64() - trace_c0) << 32);
+        t[3] = __builtin_amdgcn_s_getreg(63492) | (static_cast<long long>(__builtin_amdgcn_s_getreg(63508)) << 32);
+    }
+#endif
+}
+
+}  // namespace
+
+#ifdef ALLOCMOE_TRACE
+extern "C" int allocmoe_debug_t256_trace(long long* host_out, int n_rows) {
+    return static_cast<int>(hipMemcpyFromSymbol(host_out, HIP_SYMBOL(t256_trace),
+                                                sizeof(long long) * 4 * n_rows, 0,
+                                                hipMemcpyDeviceToHost));
+}
+#endif
+
+hipError_t launch_ffn_bf16_t256(bool swiglu, StreamGroup routed, StreamGroup shared,
+                                hipStream_t stream) {
+    const int cols = swiglu ? 128 : 256;
+    // items per XCD; for the routed group an upper bound (the real tile count is
+    // known on the device only)
+    int64_t per_xcd = 0;
+    if (routed.A != nullptr) {
+        const int64_t tiles = routed.tile_info ? routed.max_tiles : (routed.M_dense + kRows - 1) / kRows;
+        per_xcd += (tiles + kXcds - 1) / kXcds * (routed.N / cols);
+    }
+    if (shared.A != nullptr) {
+        // XCD grid over (row tiles, column tiles): xr x 8/xr, chosen to minimise the
+        // bytes the 8 L2s fetch in total: (8/xr) x activations + xr x weights
+        const int64_t rt = (shared.M_dense + kRows - 1) / kRows, ct = shared.N / cols;
+        const double a_bytes = static_cast<double>(shared.M_dense) * shared.Kd;
+        const double b_bytes = static_cast<double>(shared.N) * shared.Kd * (swiglu ? 2 : 1);
+        int best = 1;
+        double best_cost = 0;
+        for (int xr = 1; xr <= kXcds; xr *= 2) {
+            const double cost = (kXcds / xr) * a_bytes + xr * b_bytes;
+            if (xr == 1 || cost < best_cost) {
+                best = xr;
+                best_cost = cost;
+            }
+        }
+        shared.xr = best;
+        const int xc = kXcds / best;
+        per_xcd += ((rt + best - 1) / best) * ((ct + xc - 1) / xc);
+    }
+    if (per_xcd <= 0) return hipSuccess;
+    const dim3 grid(static_cast<unsigned>(per_xcd * kXcds)), block(kWaves * kWave);
+    if (swiglu)
+        hipLaunchKernelGGL(ffn_bf16_t256_kernel<true>, grid, block, 0, stream, routed, shared);
+    else
+        hipLaunchKernelGGL(ffn_bf16_t256_kernel<false>, grid, block, 0, stream, routed, shared);
+    return hipGetLastError();
+}
+
+}  // namespace allocmoe

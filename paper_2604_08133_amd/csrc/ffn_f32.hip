@@ -26,7 +26,7 @@ __global__ __launch_bounds__(256) void ffn_f32_kernel(
     int e, row0, rows;
     if (tile_info != nullptr) {
         if (tile >= tile_info[0]) return;
-        const int32_t* ent = tile_info + 4 + 4 * static_cast<size_t>(tile);
+        const int32_t* ent = tile_info + kTileHdr + 4 * static_cast<size_t>(tile);
         e = ent[0];
         row0 = ent[1];
         rows = ent[2];

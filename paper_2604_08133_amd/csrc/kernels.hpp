@@ -11,9 +11,13 @@ namespace allocmoe {
 // rows per tile of the grouped-GEMM tile map written by the plan kernel
 constexpr int kTileRowsSmall = 32;
 
-// tile_info layout: [0] = number of tiles; entry i at [4 + 4*i]: expert,
-// first row, rows in tile, 0.
-inline size_t tile_info_ints(int64_t max_tiles) { return 4 + 4 * static_cast<size_t>(max_tiles); }
+// tile_info layout: [0] = number of tiles; entry i at [kTileHdr + 4*i]: expert,
+// first row, rows in tile, 0.  Order: every full tile (expert ascending), then the
+// experts' last, partly filled tiles by decreasing row count (ties: expert
+// ascending) -- longest work first, so that a launch that takes tiles in this
+// order ends on its cheapest workgroups.
+constexpr int kTileHdr = 4;
+inline size_t tile_info_ints(int64_t max_tiles) { return kTileHdr + 4 * static_cast<size_t>(max_tiles); }
 
 // ---- route.hip
 hipError_t launch_route(int dtype, const void* X, const void* Wg, const float* bias,
@@ -68,16 +72,19 @@ struct StreamGroup {
     void* C = nullptr;
     int ldc = 0;
     int64_t n_wg = 0;          // filled by the launcher
+    int xr = 1;                // dense group: XCDs along the row tiles (filled by the launcher)
 };
 // routed experts' tiles and the shared expert's tiles in one launch
 hipError_t launch_ffn_bf16_stream(bool swiglu, StreamGroup routed, StreamGroup shared,
                                   hipStream_t stream);
 
-// Tiled variant (rows-per-tile kTileRowsLarge): needs Kd % 32 == 0 and N % 128 == 0
+// Register-blocked 256 x 256 tile kernel for prefill-shaped groups (tile map with
+// kTileRowsLarge rows per tile): weights straight from global memory into
+// registers, activations through LDS; needs Kd % 128 == 0 and N % 128 == 0
 // (swiglu) or N % 256 == 0 (plain).
 constexpr int kTileRowsLarge = 256;
-hipError_t launch_ffn_bf16_tiled(bool swiglu, StreamGroup routed, StreamGroup shared,
-                                 hipStream_t stream);
+hipError_t launch_ffn_bf16_t256(bool swiglu, StreamGroup routed, StreamGroup shared,
+                                hipStream_t stream);
 
 // ---- pack.hip : row-major [G][Kd][N] bf16 -> MFMA fragment order
 hipError_t launch_pack_b(const void* W, int G, int Kd, int N, void* out,

@@ -265,25 +265,43 @@ __device__ void dispatch_phase(PlanShared& sh, const int32_t* topk_ids,
     }
 }
 
-// Tile map of the grouped GEMMs: one entry per (expert, block of `bm` rows).
-// tile_info[0] = number of tiles; entries (expert, first row, rows) follow.
-__device__ void tilemap_phase(PlanShared& sh, int E, int bm, int32_t* __restrict__ tile_info) {
-    const int tid = threadIdx.x;
-    if (tid < kWave) {
-        const int e = tid;
-        const int rows = e < E ? sh.expert_off[e + 1] - sh.expert_off[e] : 0;
-        const int nt = (rows + bm - 1) / bm;
-        const int incl = wave_scan_incl(nt);
-        const int first = incl - nt;
-        for (int i = 0; i < nt; ++i) {
-            int32_t* ent = tile_info + 4 + 4 * static_cast<size_t>(first + i);
-            ent[0] = e;
-            ent[1] = sh.expert_off[e] + i * bm;
-            ent[2] = min(bm, rows - i * bm);
-            ent[3] = 0;
-        }
-        if (e == kWave - 1) tile_info[0] = incl;
+// Tile map of the grouped GEMMs (layout and order: kernels.hpp), written by the
+// first wave of the workgroup, lane = expert.  expert_off: the E+1 row offsets (LDS).
+__device__ __forceinline__ void write_tile_map(const int32_t* expert_off, int E, int bm,
+                                               int32_t* __restrict__ tile_info) {
+    const int e = lane_id();
+    const int rows = e < E ? expert_off[e + 1] - expert_off[e] : 0;
+    const int n_full = rows / bm, rem = rows - n_full * bm;
+    const int incl = wave_scan_incl(n_full);
+    const int total_full = __builtin_amdgcn_readlane(incl, kWave - 1);
+    const int first = incl - n_full;
+    for (int i = 0; i < n_full; ++i) {
+        int32_t* ent = tile_info + kTileHdr + 4 * static_cast<size_t>(first + i);
+        ent[0] = e;
+        ent[1] = expert_off[e] + i * bm;
+        ent[2] = bm;
+        ent[3] = 0;
     }
+    // rank of this expert's partial tile among all partial tiles
+    int rank = 0, n_partial = 0;
+#pragma unroll
+    for (int o = 0; o < kWave; ++o) {
+        const int ro = __builtin_amdgcn_readlane(rem, o);
+        rank += (ro > rem || (ro == rem && o < e)) ? 1 : 0;
+        n_partial += ro > 0 ? 1 : 0;
+    }
+    if (rem > 0) {
+        int32_t* ent = tile_info + kTileHdr + 4 * static_cast<size_t>(total_full + rank);
+        ent[0] = e;
+        ent[1] = expert_off[e] + n_full * bm;
+        ent[2] = rem;
+        ent[3] = 0;
+    }
+    if (e == 0) tile_info[0] = total_full + n_partial;
+}
+
+__device__ void tilemap_phase(PlanShared& sh, int E, int bm, int32_t* __restrict__ tile_info) {
+    if (threadIdx.x < kWave) write_tile_map(sh.expert_off, E, bm, tile_info);
 }
 
 // ---------------------------------------------------------------------------
@@ -552,21 +570,7 @@ __global__ __launch_bounds__(NT) void plan_fast_kernel(
         }
     }
     // ---- tile map
-    if (tile_info != nullptr && tid < kWave) {
-        const int e = tid;
-        const int rows = e < E ? sh.expert_off[e + 1] - sh.expert_off[e] : 0;
-        const int nt = (rows + bm - 1) / bm;
-        const int incl = wave_scan_incl(nt);
-        const int first = incl - nt;
-        for (int i = 0; i < nt; ++i) {
-            int32_t* ent = tile_info + 4 + 4 * static_cast<size_t>(first + i);
-            ent[0] = e;
-            ent[1] = sh.expert_off[e] + i * bm;
-            ent[2] = min(bm, rows - i * bm);
-            ent[3] = 0;
-        }
-        if (e == kWave - 1) tile_info[0] = incl;
-    }
+    if (tile_info != nullptr && tid < kWave) write_tile_map(sh.expert_off, E, bm, tile_info);
 }
 
 // 0: large sizes (generic kernels), 256 / 1024: block size of the fast kernel.
