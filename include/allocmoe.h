@@ -154,7 +154,12 @@ allocmoe_status allocmoe_dispatch(const allocmoe_layer_desc *desc, const int32_t
 
 /* Steps 1-6.  X device [T,d], Y device [T,d], both desc->dtype.  The
  * intermediates stay in the workspace at the offsets of
- * allocmoe_workspace_layout. */
+ * allocmoe_workspace_layout.  All work is ordered after what `stream` holds at
+ * the call and before what is enqueued on it afterwards.  For prefill-shaped
+ * calls with a shared expert the library runs that expert's first GEMM on a
+ * stream of its own (one extra stream and two events per device, created on
+ * first use, default priority) beside the selection; both ends are tied to
+ * `stream` with events, no host synchronisation. */
 allocmoe_status allocmoe_moe_forward(const allocmoe_layer_desc *desc, const void *X,
                                      const allocmoe_weights *w, void *Y, void *ws,
                                      size_t ws_bytes, allocmoe_stream stream);
@@ -169,9 +174,10 @@ typedef enum {
     ALLOCMOE_N_STAGES = 5
 } allocmoe_stage;
 
-/* Measurement variant of allocmoe_moe_forward: same work, same kernels, same
- * launch configuration, but a HIP event is recorded on the stream around every
- * stage; the call then WAITS for the last event (the one exception to the
+/* Measurement variant of allocmoe_moe_forward: same work and same kernels, but
+ * every stage runs on `stream` alone, one after the other (the shared expert's
+ * first GEMM shares a launch with the routed experts' instead of running beside
+ * the selection), and a HIP event is recorded on the stream around every stage; the call then WAITS for the last event (the one exception to the
  * no-synchronisation rule) and writes the stage durations in milliseconds to
  * stage_ms[ALLOCMOE_N_STAGES] (host memory).  The events are host objects the
  * library creates on first use and keeps; not thread-safe; for benchmarking. */

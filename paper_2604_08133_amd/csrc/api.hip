@@ -5,6 +5,8 @@
 
 #include "kernels.hpp"
 
+#include <mutex>
+
 namespace {
 
 using namespace allocmoe;
@@ -242,6 +244,35 @@ allocmoe_status allocmoe_dispatch(const allocmoe_layer_desc* desc, const int32_t
 
 namespace {
 
+// Host-side objects for running the shared expert's first GEMM beside the
+// selection: one extra stream (default priority, not synchronising with the
+// null stream) and two events without timing per device, created on first use
+// and kept for the life of the process.
+struct SideStream {
+    hipStream_t stream = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
+};
+
+allocmoe_status side_stream_of_current_device(SideStream** out) {
+    constexpr int kMaxDevices = 64;
+    static SideStream table[kMaxDevices];
+    static std::mutex lock;
+    int dev = 0;
+    ALLOCMOE_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return ALLOCMOE_EHIP;
+    std::lock_guard<std::mutex> guard(lock);
+    SideStream& s = table[dev];
+    if (s.stream == nullptr) {
+        hipStream_t st = nullptr;
+        ALLOCMOE_TRY(hipStreamCreateWithFlags(&st, hipStreamNonBlocking));
+        ALLOCMOE_TRY(hipEventCreateWithFlags(&s.fork, hipEventDisableTiming));
+        ALLOCMOE_TRY(hipEventCreateWithFlags(&s.join, hipEventDisableTiming));
+        s.stream = st;
+    }
+    *out = &s;
+    return ALLOCMOE_OK;
+}
+
 // Records ev[i] (when ev is not null) on the stream before stage i.
 #define ALLOCMOE_MARK(i)                                                  \
     do {                                                                  \
@@ -308,6 +339,20 @@ allocmoe_status forward_impl(const allocmoe_layer_desc* desc, const void* X,
     const bool shared_tiled = tiled_shapes && T >= 128;
     const int bm = routed_tiled ? kTileRowsLarge : kTileRowsSmall;
     const int64_t max_tiles = max_tiles_for(desc, bm);
+    // The shared expert does not depend on the selection: when both are big enough
+    // to matter (prefill-shaped calls), its first GEMM runs on a side stream beside
+    // the single-workgroup plan kernel and then beside the routed experts' first
+    // GEMM; the two streams meet again before the second GEMM.  The plan kernel is
+    // enqueued first so that it gets a compute unit before the GEMM fills them.
+    // The measurement variant (ev != null) keeps every stage on the caller's stream.
+    const bool overlap = ev == nullptr && routed_tiled && shared_tiled && B > 0;
+    SideStream* side = nullptr;
+    if (overlap) {
+        const allocmoe_status sst = side_stream_of_current_device(&side);
+        if (sst != ALLOCMOE_OK) return sst;
+        ALLOCMOE_TRY(hipEventRecord(side->fork, stream));
+        ALLOCMOE_TRY(hipStreamWaitEvent(side->stream, side->fork, 0));
+    }
     // steps 3-4: Alloc-T selection, dispatch, tile map
     ALLOCMOE_MARK(ALLOCMOE_STAGE_PLAN);
     ALLOCMOE_TRY(launch_plan(topk_s, topk_ids, T, K, desc->K_base, B, E, keep_count,
@@ -340,7 +385,12 @@ allocmoe_status forward_impl(const allocmoe_layer_desc* desc, const void* X,
             const StreamGroup& r = swiglu ? r1 : r2;
             const StreamGroup& sh = swiglu ? s1 : s2;
             ALLOCMOE_MARK(swiglu ? ALLOCMOE_STAGE_FFN1 : ALLOCMOE_STAGE_FFN2);
-            if (routed_tiled == shared_tiled) {   // one launch covers both groups
+            if (overlap && swiglu) {
+                ALLOCMOE_TRY(launch_ffn_bf16_t256(true, none, sh, side->stream));
+                ALLOCMOE_TRY(hipEventRecord(side->join, side->stream));
+                ALLOCMOE_TRY(launch_ffn_bf16_t256(true, r, none, stream));
+                ALLOCMOE_TRY(hipStreamWaitEvent(stream, side->join, 0));
+            } else if (routed_tiled == shared_tiled) {   // one launch covers both groups
                 ALLOCMOE_TRY(routed_tiled ? launch_ffn_bf16_t256(swiglu, r, sh, stream)
                                           : launch_ffn_bf16_stream(swiglu, r, sh, stream));
             } else {

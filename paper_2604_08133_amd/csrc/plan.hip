@@ -351,6 +351,16 @@ __device__ __forceinline__ uint64_t wave_transpose64(uint64_t x) {
     return x;
 }
 
+#ifdef ALLOCMOE_TRACE
+__device__ long long plan_trace[16];
+#define ALLOCMOE_PLAN_STAMP(i)                                   \
+    do {                                                         \
+        if (threadIdx.x == 0) plan_trace[i] = wall_clock64();    \
+    } while (0)
+#else
+#define ALLOCMOE_PLAN_STAMP(i)
+#endif
+
 template <bool SELECT, bool DISPATCH, int NT>
 __global__ __launch_bounds__(NT) void plan_fast_kernel(
     const float* topk_s, const int32_t* topk_ids, int T, int K, int Kb, int64_t B, int E,
@@ -362,6 +372,7 @@ __global__ __launch_bounds__(NT) void plan_fast_kernel(
     constexpr int NBINS_LOG2 = NT == 1024 ? 11 : 9;
     static_assert(NT == 1024 || NT == 256, "two block sizes");
     const int tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
+    ALLOCMOE_PLAN_STAMP(0);
 
     if (SELECT) {
         const int P = K - Kb;
@@ -388,6 +399,7 @@ __global__ __launch_bounds__(NT) void plan_fast_kernel(
                     }
                 }
             }
+            ALLOCMOE_PLAN_STAMP(1);
             // ---- range of the keys
             uint32_t lo = 0xFFFFFFFFu, hi = 0u;
 #pragma unroll
@@ -416,6 +428,7 @@ __global__ __launch_bounds__(NT) void plan_fast_kernel(
                 lo = min(lo, sh.red_lo[w]);
                 hi = max(hi, sh.red_hi[w]);
             }
+            ALLOCMOE_PLAN_STAMP(2);
             // ---- narrowing passes (see select_phase)
             uint32_t r = static_cast<uint32_t>(want);
             uint32_t in_range = static_cast<uint32_t>(n_pool);
@@ -454,6 +467,7 @@ __global__ __launch_bounds__(NT) void plan_fast_kernel(
                 lo = new_lo;
                 __syncthreads();
             }
+            ALLOCMOE_PLAN_STAMP(3);
             const uint32_t vstar = lo, n_equal = in_range, R = r;
             // ---- equal keys that precede this thread's slice (only if a tie is split)
             uint32_t before = 0;
@@ -497,6 +511,7 @@ __global__ __launch_bounds__(NT) void plan_fast_kernel(
         __syncthreads();
     }
     if (!DISPATCH) return;
+    ALLOCMOE_PLAN_STAMP(4);
 
     const int n_batch = (T + kWave - 1) / kWave;
     // ---- A: ballot words by bit-matrix transpose (lane e ends up with expert e's word)
@@ -516,6 +531,7 @@ __global__ __launch_bounds__(NT) void plan_fast_kernel(
         sh.words[b * kWave + lane] = wave_transpose64(mine);
     }
     __syncthreads();
+    ALLOCMOE_PLAN_STAMP(5);
     // ---- B: per expert, exclusive prefix over batches; offsets over experts
     {
         const int e = tid % kWave, seg = tid / kWave;
@@ -544,6 +560,7 @@ __global__ __launch_bounds__(NT) void plan_fast_kernel(
         __syncthreads();
         if (tid <= E) expert_offsets[tid] = sh.expert_off[tid];
     }
+    ALLOCMOE_PLAN_STAMP(6);
     // ---- C: place every pair
     for (int b = wave; b < n_batch; b += NW) {
         const int t = b * kWave + lane;
@@ -569,9 +586,18 @@ __global__ __launch_bounds__(NT) void plan_fast_kernel(
             inv_row[static_cast<size_t>(t) * K + j] = row;
         }
     }
+    ALLOCMOE_PLAN_STAMP(7);
     // ---- tile map
     if (tile_info != nullptr && tid < kWave) write_tile_map(sh.expert_off, E, bm, tile_info);
+    ALLOCMOE_PLAN_STAMP(8);
 }
+
+#ifdef ALLOCMOE_TRACE
+extern "C" int allocmoe_debug_plan_trace(long long* host_out) {
+    return static_cast<int>(hipMemcpyFromSymbol(host_out, HIP_SYMBOL(plan_trace), sizeof(long long) * 16,
+                                                0, hipMemcpyDeviceToHost));
+}
+#endif
 
 // 0: large sizes (generic kernels), 256 / 1024: block size of the fast kernel.
 // Small problems run on 4 waves (one per SIMD): the kernel is a chain of short
