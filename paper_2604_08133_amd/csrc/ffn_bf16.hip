@@ -7,11 +7,13 @@
 // rows the layer is bound by reading each active expert's weights once from
 // HBM.  A workgroup owns one (row tile of <= 32 rows, block of 32 output
 // columns); its 4 waves split the contraction dimension, each streaming its
-// slice of the packed weight fragments straight from global memory into MFMA B
+// share of the packed weight fragments straight from global memory into MFMA B
 // operands (1 KB contiguous per wave-load, every byte read once), with many
 // independent loads in flight.  The A operand (<= 32 activation rows, L2
 // resident) is gathered per lane.  Partial accumulators meet in LDS in a fixed
 // order, so results are bitwise reproducible.
+#include <type_traits>
+
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -63,15 +65,17 @@ __global__ __launch_bounds__(kStreamWaves* kWave) void ffn_bf16_stream_kernel(St
     const int lane = lane_id(), wave = threadIdx.x / kWave;
     const int KB = Kd / 16;                 // k16 steps in total
     const int steps = KB / kStreamWaves;    // per wave (Kd is a multiple of 64)
-    const int kb0 = wave * steps;
+    // The waves take the k16 steps round-robin (wave w: steps w, w+4, ...), so at
+    // any time the workgroup reads one contiguous run of each weight stream.
 
     // packed B: for this expert and column block, KB fragments of 64 x bf16x8
     // (W1 stream, then for SWIGLU the W3 stream)
     const bf16x8* b1 = reinterpret_cast<const bf16x8*>(
                            Bp + static_cast<size_t>(e) * group_stride +
                            static_cast<size_t>(nb) * (static_cast<size_t>(NACC) * Kd * 32)) +
-                       static_cast<size_t>(kb0) * kWave + lane;
+                       static_cast<size_t>(wave) * kWave + lane;
     const bf16x8* b3 = b1 + static_cast<size_t>(KB) * kWave;
+    constexpr size_t kStepB = static_cast<size_t>(kStreamWaves) * kWave;   // fragments per round
 
     // A: lane (m = l%32, kg = l/32) reads 8 consecutive k of its row per step
     const int m = lane % 32, kg = lane / 32;
@@ -82,33 +86,40 @@ __global__ __launch_bounds__(kStreamWaves* kWave) void ffn_bf16_stream_kernel(St
         src = row_map ? row_map[r] : r;
     }
     const bf16x8* ap =
-        reinterpret_cast<const bf16x8*>(A + static_cast<size_t>(src) * lda) + kb0 * 2 + kg;
+        reinterpret_cast<const bf16x8*>(A + static_cast<size_t>(src) * lda) + wave * 2 + kg;
+    constexpr int kStepA = kStreamWaves * 2;
 
     f32x16 acc1 = {0}, acc3 = {0};
     const bf16x8 zero = {0};
-    int s = 0;
-    for (; s + kStreamUnroll <= steps; s += kStreamUnroll) {
-        bf16x8 av[kStreamUnroll], w1[kStreamUnroll], w3[kStreamUnroll];
+    // a batch of N steps: all loads first (they are in flight together), then the MFMAs
+    auto batch = [&](int s, auto n_const) {
+        constexpr int N = decltype(n_const)::value;
+        bf16x8 av[N], w1[N], w3[N];
 #pragma unroll
-        for (int u = 0; u < kStreamUnroll; ++u) {
-            w1[u] = __builtin_nontemporal_load(b1 + static_cast<size_t>(s + u) * kWave);
-            if (SWIGLU) w3[u] = __builtin_nontemporal_load(b3 + static_cast<size_t>(s + u) * kWave);
-            av[u] = a_ok ? ap[(s + u) * 2] : zero;
+        for (int u = 0; u < N; ++u) {
+            w1[u] = __builtin_nontemporal_load(b1 + static_cast<size_t>(s + u) * kStepB);
+            if (SWIGLU) w3[u] = __builtin_nontemporal_load(b3 + static_cast<size_t>(s + u) * kStepB);
+            av[u] = a_ok ? ap[(s + u) * kStepA] : zero;
         }
 #pragma unroll
-        for (int u = 0; u < kStreamUnroll; ++u) {
+        for (int u = 0; u < N; ++u) {
             acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[u], w1[u], acc1, 0, 0, 0);
             if (SWIGLU) acc3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[u], w3[u], acc3, 0, 0, 0);
         }
-    }
-    for (; s < steps; ++s) {
-        const bf16x8 w1 = __builtin_nontemporal_load(b1 + static_cast<size_t>(s) * kWave);
-        const bf16x8 av = a_ok ? ap[s * 2] : zero;
-        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, w1, acc1, 0, 0, 0);
-        if (SWIGLU) {
-            const bf16x8 w3 = __builtin_nontemporal_load(b3 + static_cast<size_t>(s) * kWave);
-            acc3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, w3, acc3, 0, 0, 0);
-        }
+    };
+    int s = 0;
+    for (; s + kStreamUnroll <= steps; s += kStreamUnroll)
+        batch(s, std::integral_constant<int, kStreamUnroll>{});
+    static_assert(kStreamUnroll == 8, "the switch below lists the short last batches");
+    switch (steps - s) {   // uniform
+        case 7: batch(s, std::integral_constant<int, 7>{}); break;
+        case 6: batch(s, std::integral_constant<int, 6>{}); break;
+        case 5: batch(s, std::integral_constant<int, 5>{}); break;
+        case 4: batch(s, std::integral_constant<int, 4>{}); break;
+        case 3: batch(s, std::integral_constant<int, 3>{}); break;
+        case 2: batch(s, std::integral_constant<int, 2>{}); break;
+        case 1: batch(s, std::integral_constant<int, 1>{}); break;
+        default: break;
     }
 
 #pragma unroll

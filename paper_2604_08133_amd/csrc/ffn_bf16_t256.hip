@@ -76,7 +76,7 @@ __device__ __forceinline__ void wait_vmcnt_le() {
     __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
-template <bool SWIGLU, int NRB>
+template <bool SWIGLU, int NRB, bool STREAM_ONCE>
 __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda,
                                           const int32_t* row_map, const bf16x8* b0,
                                           const bf16x8* b1, int KT, int wave, int lane, int row0,
@@ -110,8 +110,15 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
     const int KQ = 4 * KT;   // k16 steps in total
     bf16x8 breg[kBRing][2];
     auto load_b = [&](int q, int r) {
-        breg[r][0] = b0[static_cast<size_t>(q) * kWave];
-        breg[r][1] = b1[static_cast<size_t>(q) * kWave];
+        // weights that no other tile reads are marked non-temporal: they need not
+        // displace what the caches hold for tiles that share theirs
+        if (STREAM_ONCE) {
+            breg[r][0] = __builtin_nontemporal_load(b0 + static_cast<size_t>(q) * kWave);
+            breg[r][1] = __builtin_nontemporal_load(b1 + static_cast<size_t>(q) * kWave);
+        } else {
+            breg[r][0] = b0[static_cast<size_t>(q) * kWave];
+            breg[r][1] = b1[static_cast<size_t>(q) * kWave];
+        }
     };
     // A operand of row block i, k16 chunk kc of a slot: lane l reads row m = l%32 of
     // the block, 16-byte chunk c = 2 kc + l/32 of that row, stored at position
@@ -260,15 +267,18 @@ __global__ __launch_bounds__(kWaves* kWave, 1) void ffn_bf16_t256_kernel(StreamG
     const int32_t* __restrict__ tile_info = g.tile_info;
     const int lda = g.lda, Kd = g.Kd, ldc = g.ldc, M_dense = g.M_dense;
     int e, row0, rows;
+    bool only_tile;   // of its expert: nobody else reads these weights
     if (tile_info != nullptr) {
         const int32_t* ent = tile_info + kTileHdr + 4 * static_cast<size_t>(tile);
         e = ent[0];
         row0 = ent[1];
         rows = ent[2];
+        only_tile = ent[3] == 1;
     } else {
         e = 0;
         row0 = tile * kRows;
         rows = min(kRows, M_dense - row0);
+        only_tile = M_dense <= kRows;
     }
     const int lane = lane_id(), wave = threadIdx.x / kWave;
     const int n_rb = (rows + 31) / 32;   // 32-row blocks that hold real rows
@@ -286,8 +296,15 @@ __global__ __launch_bounds__(kWaves* kWave, 1) void ffn_bf16_t256_kernel(StreamG
                            Bp + static_cast<size_t>(e) * g.group_stride + sidx * stream_elems) + lane;
     const bf16x8* b1 = b0 + stream_elems / 8;
 
-#define ALLOCMOE_T256_CASE(n) \
-    case n: t256_body<SWIGLU, n>(lds, A, lda, row_map, b0, b1, KT, wave, lane, row0, rows, nt, g.C, ldc); break;
+#define ALLOCMOE_T256_CASE(n)                                                                       \
+    case n:                                                                                         \
+        if (only_tile)                                                                              \
+            t256_body<SWIGLU, n, true>(lds, A, lda, row_map, b0, b1, KT, wave, lane, row0, rows, nt, \
+                                       g.C, ldc);                                                   \
+        else                                                                                        \
+            t256_body<SWIGLU, n, false>(lds, A, lda, row_map, b0, b1, KT, wave, lane, row0, rows,   \
+                                        nt, g.C, ldc);                                              \
+        break;
     switch (n_rb) {   // uniform over the workgroup
         ALLOCMOE_T256_CASE(1)
         ALLOCMOE_T256_CASE(2)
@@ -296,7 +313,7 @@ __global__ __launch_bounds__(kWaves* kWave, 1) void ffn_bf16_t256_kernel(StreamG
         ALLOCMOE_T256_CASE(5)
         ALLOCMOE_T256_CASE(6)
         ALLOCMOE_T256_CASE(7)
-        default: t256_body<SWIGLU, 8>(lds, A, lda, row_map, b0, b1, KT, wave, lane, row0, rows, nt, g.C, ldc); break;
+        default: ALLOCMOE_T256_CASE(8)
     }
 #undef ALLOCMOE_T256_CASE
 #ifdef ALLOCMOE_TRACE

@@ -12,7 +12,7 @@ namespace allocmoe {
 constexpr int kTileRowsSmall = 32;
 
 // tile_info layout: [0] = number of tiles; entry i at [kTileHdr + 4*i]: expert,
-// first row, rows in tile, 0.  Order: every full tile (expert ascending), then the
+// first row, rows in tile, number of tiles of this expert.  Order: every full tile (expert ascending), then the
 // experts' last, partly filled tiles by decreasing row count (ties: expert
 // ascending) -- longest work first, so that a launch that takes tiles in this
 // order ends on its cheapest workgroups.

@@ -280,7 +280,7 @@ __device__ __forceinline__ void write_tile_map(const int32_t* expert_off, int E,
         ent[0] = e;
         ent[1] = expert_off[e] + i * bm;
         ent[2] = bm;
-        ent[3] = 0;
+        ent[3] = n_full + (rem > 0 ? 1 : 0);
     }
     // rank of this expert's partial tile among all partial tiles
     int rank = 0, n_partial = 0;
@@ -295,7 +295,7 @@ __device__ __forceinline__ void write_tile_map(const int32_t* expert_off, int E,
         ent[0] = e;
         ent[1] = expert_off[e] + n_full * bm;
         ent[2] = rem;
-        ent[3] = 0;
+        ent[3] = n_full + 1;
     }
     if (e == 0) tile_info[0] = total_full + n_partial;
 }
