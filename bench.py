@@ -202,7 +202,7 @@ def main():
         roof = {"bound": "hbm", "achieved": ffn1_bytes / (dom_ms * 1e-3) / 1e9,
                 "peak": HBM_PEAK_GBS, "unit": "GB/s"}
     else:
-        kernel_name = "ffn_bf16_tiled_kernel<true>"
+        kernel_name = "ffn_bf16_t256_kernel<true>"
         roof = {"bound": "mfma", "achieved": ffn1_flops / (dom_ms * 1e-3) / 1e12,
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s"}
         # what the roofline allows at this arithmetic intensity: min(peak, flop/byte x HBM)

@@ -233,9 +233,12 @@ __global__ __launch_bounds__(kWaves* kWave, 1) void ffn_bf16_t256_kernel(StreamG
     //    first round start together and stay in step, so a weight stream is fetched
     //    into an L2 once for all the XCD's row tiles, an activation tile once for
     //    all its column tiles.
-    //  * Then the routed tiles in the tile map's order (longest first), tile t on
-    //    XCD t % 8 with its column tiles back to back (they share the gathered
-    //    activation rows).  The launch ends on the cheapest workgroups.
+    //  * Then the routed tiles in the tile map's order (longest first), in pairs of
+    //    neighbours: pair p runs on XCD p % 8, its items ordered (column tile, tile
+    //    of the pair).  Neighbouring tiles mostly belong to one expert and cost the
+    //    same, so the two workgroups of a column tile start together and share one
+    //    pass over the weight stream; the column tiles that share the gathered
+    //    activation rows follow within a few items.
     constexpr int kColsPerTile = SWIGLU ? 128 : 256;
     const int xcd = blockIdx.x % kXcds, idx = blockIdx.x / kXcds;
     const int nt0 = g0.A ? g0.N / kColsPerTile : 1, nt1 = g1.A ? g1.N / kColsPerTile : 1;
@@ -251,11 +254,19 @@ __global__ __launch_bounds__(kWaves* kWave, 1) void ffn_bf16_t256_kernel(StreamG
     int tile, nt;
     if (first) {
         if (g0.A == nullptr) return;
-        const int sub = idx - S;
-        const int tiles = g0.tile_info ? g0.tile_info[0] : (g0.M_dense + kRows - 1) / kRows;
-        tile = sub / nt0 * kXcds + xcd;
-        nt = sub % nt0;
-        if (tile >= tiles) return;   // the grid is sized for the host's bound
+        int sub = idx - S;
+        if (g0.tile_info != nullptr) {
+            const int tiles = g0.tile_info[0];
+            const int pair = sub / (2 * nt0) * kXcds + xcd, in_pair = sub % (2 * nt0);
+            tile = 2 * pair + in_pair % 2;
+            nt = in_pair / 2;
+            if (tile >= tiles) return;   // the grid is sized for the host's bound
+        } else {   // a dense group in the first slot: its row tiles striped over the XCDs
+            const int tiles = (g0.M_dense + kRows - 1) / kRows;
+            tile = sub / nt0 * kXcds + xcd;
+            nt = sub % nt0;
+            if (tile >= tiles) return;
+        }
     } else {
         tile = xri + xr * (idx % s_rows);
         nt = xci + xc * (idx / s_rows);
@@ -344,8 +355,12 @@ hipError_t launch_ffn_bf16_t256(bool swiglu, StreamGroup routed, StreamGroup sha
     // known on the device only)
     int64_t per_xcd = 0;
     if (routed.A != nullptr) {
-        const int64_t tiles = routed.tile_info ? routed.max_tiles : (routed.M_dense + kRows - 1) / kRows;
-        per_xcd += (tiles + kXcds - 1) / kXcds * (routed.N / cols);
+        int64_t tiles;   // per XCD
+        if (routed.tile_info != nullptr)
+            tiles = 2 * (((routed.max_tiles + 1) / 2 + kXcds - 1) / kXcds);   // whole pairs
+        else
+            tiles = ((routed.M_dense + kRows - 1) / kRows + kXcds - 1) / kXcds;
+        per_xcd += tiles * (routed.N / cols);
     }
     if (shared.A != nullptr) {
         // XCD grid over (row tiles, column tiles): xr x 8/xr, chosen to minimise the

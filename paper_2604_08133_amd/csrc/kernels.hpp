@@ -12,10 +12,13 @@ namespace allocmoe {
 constexpr int kTileRowsSmall = 32;
 
 // tile_info layout: [0] = number of tiles; entry i at [kTileHdr + 4*i]: expert,
-// first row, rows in tile, number of tiles of this expert.  Order: every full tile (expert ascending), then the
-// experts' last, partly filled tiles by decreasing row count (ties: expert
-// ascending) -- longest work first, so that a launch that takes tiles in this
-// order ends on its cheapest workgroups.
+// first row, rows in tile, number of tiles of this expert.
+//
+// An expert's rows are split evenly over its ceil(rows / bm) tiles, so the tiles
+// of one expert cost the same.  Experts are listed by decreasing rows per tile
+// (ties: expert ascending), an expert's tiles next to each other: a launch that
+// takes tiles in this order starts with its longest workgroups and ends on its
+// cheapest, and neighbouring tiles mostly read the same expert's weights.
 constexpr int kTileHdr = 4;
 inline size_t tile_info_ints(int64_t max_tiles) { return kTileHdr + 4 * static_cast<size_t>(max_tiles); }
 

@@ -266,38 +266,40 @@ __device__ void dispatch_phase(PlanShared& sh, const int32_t* topk_ids,
 }
 
 // Tile map of the grouped GEMMs (layout and order: kernels.hpp), written by the
-// first wave of the workgroup, lane = expert.  expert_off: the E+1 row offsets (LDS).
+// first wave of the workgroup.  expert_off: the E+1 row offsets (LDS).
 __device__ __forceinline__ void write_tile_map(const int32_t* expert_off, int E, int bm,
                                                int32_t* __restrict__ tile_info) {
-    const int e = lane_id();
-    const int rows = e < E ? expert_off[e + 1] - expert_off[e] : 0;
-    const int n_full = rows / bm, rem = rows - n_full * bm;
-    const int incl = wave_scan_incl(n_full);
-    const int total_full = __builtin_amdgcn_readlane(incl, kWave - 1);
-    const int first = incl - n_full;
-    for (int i = 0; i < n_full; ++i) {
-        int32_t* ent = tile_info + kTileHdr + 4 * static_cast<size_t>(first + i);
-        ent[0] = e;
-        ent[1] = expert_off[e] + i * bm;
-        ent[2] = bm;
-        ent[3] = n_full + (rem > 0 ? 1 : 0);
-    }
-    // rank of this expert's partial tile among all partial tiles
-    int rank = 0, n_partial = 0;
+    const int lane = lane_id();
+    // lane = expert: its rows in n tiles of rt rows (the last one may hold fewer)
+    int rows = lane < E ? expert_off[lane + 1] - expert_off[lane] : 0;
+    int off = lane < E ? expert_off[lane] : 0;
+    int n = (rows + bm - 1) / bm;
+    int rt = n > 0 ? (rows + n - 1) / n : 0;
+    // rank of the expert by (rows per tile descending, expert ascending)
+    int rank = 0;
 #pragma unroll
     for (int o = 0; o < kWave; ++o) {
-        const int ro = __builtin_amdgcn_readlane(rem, o);
-        rank += (ro > rem || (ro == rem && o < e)) ? 1 : 0;
-        n_partial += ro > 0 ? 1 : 0;
+        const int ro = __builtin_amdgcn_readlane(rt, o);
+        rank += (ro > rt || (ro == rt && o < lane)) ? 1 : 0;
     }
-    if (rem > 0) {
-        int32_t* ent = tile_info + kTileHdr + 4 * static_cast<size_t>(total_full + rank);
+    // from here on lane = rank: fetch the data of the expert with this rank
+    int e = 0;
+#pragma unroll
+    for (int o = 0; o < kWave; ++o) e = __builtin_amdgcn_readlane(rank, o) == lane ? o : e;
+    rows = __shfl(rows, e, kWave);
+    off = __shfl(off, e, kWave);
+    n = __shfl(n, e, kWave);
+    rt = __shfl(rt, e, kWave);
+    const int incl = wave_scan_incl(n);
+    const int first = incl - n;
+    for (int i = 0; i < n; ++i) {
+        int32_t* ent = tile_info + kTileHdr + 4 * static_cast<size_t>(first + i);
         ent[0] = e;
-        ent[1] = expert_off[e] + n_full * bm;
-        ent[2] = rem;
-        ent[3] = n_full + 1;
+        ent[1] = off + i * rt;
+        ent[2] = min(rt, rows - i * rt);
+        ent[3] = n;
     }
-    if (e == 0) tile_info[0] = total_full + n_partial;
+    if (lane == kWave - 1) tile_info[0] = incl;
 }
 
 __device__ void tilemap_phase(PlanShared& sh, int E, int bm, int32_t* __restrict__ tile_info) {
