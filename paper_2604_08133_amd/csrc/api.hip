@@ -319,6 +319,55 @@ allocmoe_status forward_impl(const allocmoe_layer_desc* desc, const void* X,
     float* O = at<float>(base, L.O);
     float* Os = Is ? at<float>(base, L.Os) : nullptr;
 
+    // Kernel choice for step 5 (bf16): experts that see tens of rows or more use
+    // the register-blocked tile kernel (256-row tiles), otherwise the
+    // weight-streaming kernel (32-row tiles); decided per group from the descriptor
+    // alone.
+    const bool tiled_shapes = bf16 && d % 256 == 0 && I % 128 == 0 && Is % 128 == 0;
+    const bool routed_tiled = tiled_shapes && B >= 24 * static_cast<int64_t>(E);
+    const bool shared_tiled = tiled_shapes && T >= 128;
+    const int bm = routed_tiled ? kTileRowsLarge : kTileRowsSmall;
+    const int64_t max_tiles = max_tiles_for(desc, bm);
+    // The shared expert depends on nothing but X: its two GEMMs run on a side stream
+    // beside routing, selection and the routed experts' GEMMs, and the streams meet
+    // again before the combine.  Where the shared expert's GEMM fills the machine
+    // (tile kernel), the side stream starts after the routing kernel and the
+    // single-workgroup plan kernel is enqueued first, so that it gets a compute
+    // unit at once.  The measurement variant (ev != null) keeps every stage on the
+    // caller's stream.
+    const bool overlap = ev == nullptr && bf16 && Is > 0 && B > 0;
+    SideStream* side = nullptr;
+    StreamGroup s1, s2;   // the shared expert's two GEMMs
+    if (bf16 && Is) {
+        const PackedLayout p = packed_of(desc);
+        const uint16_t* pk = static_cast<const uint16_t*>(w->packed);
+        const size_t dd = d, SS = Is;
+        s1.A = X; s1.lda = d; s1.Bp = pk + p.ps13; s1.group_stride = 2 * dd * SS; s1.Kd = d;
+        s1.N = Is; s1.M_dense = T; s1.C = Hs; s1.ldc = Is;
+        s2.A = Hs; s2.lda = Is; s2.Bp = pk + p.ps2; s2.group_stride = SS * dd; s2.Kd = Is;
+        s2.N = d; s2.M_dense = T; s2.C = Os; s2.ldc = d;
+    }
+    const StreamGroup none;
+    auto fork_shared_expert = [&]() -> allocmoe_status {
+        ALLOCMOE_TRY(hipEventRecord(side->fork, stream));
+        ALLOCMOE_TRY(hipStreamWaitEvent(side->stream, side->fork, 0));
+        for (int half = 0; half < 2; ++half) {
+            const StreamGroup& sh = half == 0 ? s1 : s2;
+            ALLOCMOE_TRY(shared_tiled ? launch_ffn_bf16_t256(half == 0, none, sh, side->stream)
+                                      : launch_ffn_bf16_stream(half == 0, sh, none, side->stream));
+        }
+        ALLOCMOE_TRY(hipEventRecord(side->join, side->stream));
+        return ALLOCMOE_OK;
+    };
+    if (overlap) {
+        const allocmoe_status sst = side_stream_of_current_device(&side);
+        if (sst != ALLOCMOE_OK) return sst;
+        if (!shared_tiled) {
+            const allocmoe_status fst = fork_shared_expert();
+            if (fst != ALLOCMOE_OK) return fst;
+        }
+    }
+
     // steps 1-2: scores and sorted candidates
     ALLOCMOE_MARK(ALLOCMOE_STAGE_ROUTE);
     if (bf16) {
@@ -330,26 +379,7 @@ allocmoe_status forward_impl(const allocmoe_layer_desc* desc, const void* X,
                                   desc->shared_gate ? w->w_sg : nullptr, T, d, E, K, scores,
                                   topk_ids, topk_s, sgate, stream));
     }
-    // Kernel choice for step 5 (bf16): experts that see tens of rows or more use
-    // the register-blocked tile kernel (256-row tiles), otherwise the
-    // weight-streaming kernel (32-row tiles); decided per group from the descriptor
-    // alone.
-    const bool tiled_shapes = bf16 && d % 256 == 0 && I % 128 == 0 && Is % 128 == 0;
-    const bool routed_tiled = tiled_shapes && B >= 24 * static_cast<int64_t>(E);
-    const bool shared_tiled = tiled_shapes && T >= 128;
-    const int bm = routed_tiled ? kTileRowsLarge : kTileRowsSmall;
-    const int64_t max_tiles = max_tiles_for(desc, bm);
-    // The shared expert does not depend on the selection: when both are big enough
-    // to matter (prefill-shaped calls), its first GEMM runs on a side stream beside
-    // the single-workgroup plan kernel and then beside the routed experts' first
-    // GEMM; the two streams meet again before the second GEMM.  The plan kernel is
-    // enqueued first so that it gets a compute unit before the GEMM fills them.
-    // The measurement variant (ev != null) keeps every stage on the caller's stream.
-    const bool overlap = ev == nullptr && routed_tiled && shared_tiled && B > 0;
-    SideStream* side = nullptr;
-    if (overlap) {
-        const allocmoe_status sst = side_stream_of_current_device(&side);
-        if (sst != ALLOCMOE_OK) return sst;
+    if (overlap && shared_tiled) {   // the fork point; the kernels follow the plan kernel
         ALLOCMOE_TRY(hipEventRecord(side->fork, stream));
         ALLOCMOE_TRY(hipStreamWaitEvent(side->stream, side->fork, 0));
     }
@@ -359,13 +389,19 @@ allocmoe_status forward_impl(const allocmoe_layer_desc* desc, const void* X,
                              expert_offsets, row_token, row_rank, inv_row,
                              at<uint64_t>(scr, s.words), at<int32_t>(scr, s.prefix), bm, tile_info,
                              stream));
+    if (overlap && shared_tiled) {
+        for (int half = 0; half < 2; ++half)
+            ALLOCMOE_TRY(launch_ffn_bf16_t256(half == 0, none, half == 0 ? s1 : s2, side->stream));
+        ALLOCMOE_TRY(hipEventRecord(side->join, side->stream));
+    }
     // step 5: expert networks over the selected rows, then the shared expert
     if (bf16) {
         const PackedLayout p = packed_of(desc);
         const uint16_t* pk = static_cast<const uint16_t*>(w->packed);
-        const size_t dd = d, II = I, SS = Is;
-        // routed rows and the shared expert's rows share one launch per half
-        StreamGroup r1, s1, r2, s2;
+        const size_t dd = d, II = I;
+        // without the side stream, routed rows and the shared expert's rows share one
+        // launch per half where they use the same kernel
+        StreamGroup r1, r2;
         if (B > 0) {
             r1.A = X; r1.lda = d; r1.row_map = row_token; r1.Bp = pk + p.p13;
             r1.group_stride = 2 * dd * II; r1.Kd = d; r1.N = I; r1.tile_info = tile_info;
@@ -373,23 +409,14 @@ allocmoe_status forward_impl(const allocmoe_layer_desc* desc, const void* X,
             r2.A = H; r2.lda = I; r2.Bp = pk + p.p2; r2.group_stride = II * dd; r2.Kd = I;
             r2.N = d; r2.tile_info = tile_info; r2.max_tiles = max_tiles; r2.C = O; r2.ldc = d;
         }
-        if (Is) {
-            s1.A = X; s1.lda = d; s1.Bp = pk + p.ps13; s1.group_stride = 2 * dd * SS; s1.Kd = d;
-            s1.N = Is; s1.M_dense = T; s1.C = Hs; s1.ldc = Is;
-            s2.A = Hs; s2.lda = Is; s2.Bp = pk + p.ps2; s2.group_stride = SS * dd; s2.Kd = Is;
-            s2.N = d; s2.M_dense = T; s2.C = Os; s2.ldc = d;
-        }
-        const StreamGroup none;
         for (int half = 0; half < 2; ++half) {
             const bool swiglu = half == 0;
             const StreamGroup& r = swiglu ? r1 : r2;
             const StreamGroup& sh = swiglu ? s1 : s2;
             ALLOCMOE_MARK(swiglu ? ALLOCMOE_STAGE_FFN1 : ALLOCMOE_STAGE_FFN2);
-            if (overlap && swiglu) {
-                ALLOCMOE_TRY(launch_ffn_bf16_t256(true, none, sh, side->stream));
-                ALLOCMOE_TRY(hipEventRecord(side->join, side->stream));
-                ALLOCMOE_TRY(launch_ffn_bf16_t256(true, r, none, stream));
-                ALLOCMOE_TRY(hipStreamWaitEvent(stream, side->join, 0));
+            if (overlap) {
+                ALLOCMOE_TRY(routed_tiled ? launch_ffn_bf16_t256(swiglu, r, none, stream)
+                                          : launch_ffn_bf16_stream(swiglu, r, none, stream));
             } else if (routed_tiled == shared_tiled) {   // one launch covers both groups
                 ALLOCMOE_TRY(routed_tiled ? launch_ffn_bf16_t256(swiglu, r, sh, stream)
                                           : launch_ffn_bf16_stream(swiglu, r, sh, stream));
@@ -400,6 +427,7 @@ allocmoe_status forward_impl(const allocmoe_layer_desc* desc, const void* X,
                                           : launch_ffn_bf16_stream(swiglu, sh, none, stream));
             }
         }
+        if (overlap) ALLOCMOE_TRY(hipStreamWaitEvent(stream, side->join, 0));
     } else {
         const float* Xf = static_cast<const float*>(X);
         ALLOCMOE_MARK(ALLOCMOE_STAGE_FFN1);

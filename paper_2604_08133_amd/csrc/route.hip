@@ -13,26 +13,25 @@ namespace allocmoe {
 constexpr int kRouteTok = 4;    // tokens per workgroup
 constexpr int kRouteWaves = 4;  // waves per workgroup, splitting d
 
-// Wave-wide descending Top-K of one value per lane (lanes >= E hold nothing).
-// Lane j < K returns the j-th winner's lane (expert id) and value.
-__device__ __forceinline__ void wave_topk(float score, bool valid, int K, int& out_id,
-                                          float& out_s) {
+// Sorted Top-K of one token's scores, lane = expert: larger score first, equal
+// scores lower expert first.  Every lane counts the lanes that precede it in
+// that order (its rank), and the lanes with rank < K store their (expert, score)
+// at position rank of the token's candidate row.
+__device__ __forceinline__ void wave_topk_store(float score, bool valid, int K,
+                                                int32_t* __restrict__ ids_row,
+                                                float* __restrict__ s_row) {
     const int lane = lane_id();
-    // larger score first; equal scores: lower lane first
-    uint64_t key = valid ? ((static_cast<uint64_t>(ordered_key(score)) << 32) |
-                            static_cast<uint32_t>(kWave - lane))
-                         : 0ull;
-    out_id = 0;
-    out_s = 0.f;
-    for (int j = 0; j < K; ++j) {
-        uint64_t best = wave_max_u64(key);
-        int win = kWave - static_cast<int>(best & 0xFFFFFFFFull);
-        float ws = __shfl(score, win, kWave);
-        if (lane == j) {
-            out_id = win;
-            out_s = ws;
-        }
-        if (lane == win) key = 0ull;
+    // valid lanes: key >= 1 (scores are >= 0, so ordered_key has its top bit set)
+    const uint32_t key = valid ? ordered_key(score) : 0u;
+    int rank = 0;
+#pragma unroll
+    for (int o = 0; o < kWave; ++o) {
+        const uint32_t ko = __builtin_amdgcn_readlane(key, o);
+        rank += (ko > key || (ko == key && o < lane)) ? 1 : 0;
+    }
+    if (valid && rank < K) {
+        ids_row[rank] = lane;
+        s_row[rank] = score;
     }
 }
 
@@ -107,13 +106,8 @@ __global__ __launch_bounds__(kRouteWaves* kWave) void route_kernel(
         const float den = wave_sum(p);
         const float s = p / den;
         if (scores != nullptr && lane_is_expert) scores[static_cast<size_t>(t) * E + lane] = s;
-        int id;
-        float sv;
-        wave_topk(s, lane_is_expert, K, id, sv);
-        if (lane < K) {
-            topk_ids[static_cast<size_t>(t) * K + lane] = id;
-            topk_s[static_cast<size_t>(t) * K + lane] = sv;
-        }
+        wave_topk_store(s, lane_is_expert, K, topk_ids + static_cast<size_t>(t) * K,
+                        topk_s + static_cast<size_t>(t) * K);
         if (w_sg != nullptr && lane == 0) {
             float g = 0.f;
 #pragma unroll
@@ -208,13 +202,8 @@ __global__ __launch_bounds__(kRmWaves* kWave) void route_mfma_kernel(
         const float den = wave_sum(p);
         const float sc = p / den;
         if (scores != nullptr && lane_is_expert) scores[static_cast<size_t>(t) * E + lane] = sc;
-        int id;
-        float sv;
-        wave_topk(sc, lane_is_expert, K, id, sv);
-        if (lane < K) {
-            topk_ids[static_cast<size_t>(t) * K + lane] = id;
-            topk_s[static_cast<size_t>(t) * K + lane] = sv;
-        }
+        wave_topk_store(sc, lane_is_expert, K, topk_ids + static_cast<size_t>(t) * K,
+                        topk_s + static_cast<size_t>(t) * K);
         if (GATE && lane == 0) {
             float g = 0.f;
 #pragma unroll
@@ -259,13 +248,8 @@ __global__ __launch_bounds__(256) void topk_from_scores_kernel(
     if (t >= T) return;
     const bool valid = lane < E;
     const float s = valid ? scores[static_cast<size_t>(t) * E + lane] : 0.f;
-    int id;
-    float sv;
-    wave_topk(s, valid, K, id, sv);
-    if (lane < K) {
-        topk_ids[static_cast<size_t>(t) * K + lane] = id;
-        topk_s[static_cast<size_t>(t) * K + lane] = sv;
-    }
+    wave_topk_store(s, valid, K, topk_ids + static_cast<size_t>(t) * K,
+                    topk_s + static_cast<size_t>(t) * K);
 }
 
 hipError_t launch_route(int dtype, const void* X, const void* Wg, const float* bias,
