@@ -319,6 +319,7 @@ __device__ void tilemap_phase(PlanShared& sh, int E, int bm, int32_t* __restrict
 // transposed with a 6-stage butterfly of lane exchanges instead of 64 ballots.
 constexpr int kFastMaxT = 8192;
 constexpr int kFastMaxKeys = 48;
+constexpr int kDirectPool = 384;   // pools up to this size are ranked directly
 constexpr int kMaxK = 16;          // candidates per token the interface allows
 
 struct FastShared {
@@ -383,6 +384,24 @@ __global__ __launch_bounds__(NT) void plan_fast_kernel(
         if (want <= 0 || want >= n_pool) {
             const int c = want <= 0 ? Kb : K;
             for (int t = tid; t < T; t += NT) sh.cnt[t] = c;
+        } else if (n_pool <= kDirectPool) {
+            // Small pool (decode-shaped calls): every pool entry counts the entries that
+            // precede it in the order (score descending, token ascending, rank
+            // ascending) and is kept iff fewer than B' do.
+            for (int t = tid; t < T; t += NT) sh.cnt[t] = Kb;
+            for (int i = tid; i < n_pool; i += NT)
+                sh.hist[i] = ordered_key(topk_s[static_cast<size_t>(i / P) * K + Kb + i % P]);
+            __syncthreads();
+            for (int i = tid; i < n_pool; i += NT) {
+                const uint32_t k = sh.hist[i];
+                int before = 0;
+#pragma unroll 8
+                for (int o = 0; o < n_pool; ++o) {
+                    const uint32_t ko = sh.hist[o];
+                    before += (ko > k || (ko == k && o < i)) ? 1 : 0;
+                }
+                if (before < want) atomicAdd(&sh.cnt[i / P], 1);   // integer adds: order-free
+            }
         } else {
             for (int t = tid; t < T; t += NT) sh.cnt[t] = Kb;
             // ---- this thread's slice of the pool, in (token, rank) order

@@ -67,7 +67,9 @@ def test_bit_exact_distinct_scores(T, E, K, Kb):
 
 @pytest.mark.parametrize("levels", [4, 64, 1024])
 @pytest.mark.parametrize("T,E,K,Kb", [(200, 16, 4, 1), (3000, 64, 6, 1), (3000, 64, 6, 0),
-                                      (2049, 60, 4, 2), (8192, 64, 6, 1), (9500, 64, 6, 1)])
+                                      (2049, 60, 4, 2), (8192, 64, 6, 1), (9500, 64, 6, 1),
+                                      # pools small enough for the direct-ranking selection
+                                      (40, 16, 4, 1), (32, 64, 6, 1), (64, 8, 2, 0), (60, 16, 4, 0)])
 def test_bit_exact_with_ties(levels, T, E, K, Kb):
     scores = synth.make_scores(T, E, seed=levels + T, quantize_levels=levels)
     for budget in budgets_for(T, K, Kb) + [T * Kb + T // 3]:
@@ -76,11 +78,12 @@ def test_bit_exact_with_ties(levels, T, E, K, Kb):
                     oracle_route_dispatch(scores, K, Kb, budget), (levels, T, budget))
 
 
-def test_all_scores_equal():
-    T, E, K = 2500, 64, 6
+@pytest.mark.parametrize("T", [2500, 48])
+def test_all_scores_equal(T):
+    E, K = 64, 6
     scores = torch.full((T, E), 1.0 / E, dtype=torch.float32)
     for Kb, budget in [(1, T + 1), (1, 3 * T + 11), (0, 17), (2, 5 * T), (1, 6 * T - 1)]:
-        print(f"equal Kb={Kb} B={budget}", flush=True)
+        print(f"equal T={T} Kb={Kb} B={budget}", flush=True)
         assert_same(gpu_route_dispatch(scores, K, Kb, budget),
                     oracle_route_dispatch(scores, K, Kb, budget), (Kb, budget))
 
