@@ -331,9 +331,17 @@ struct FastShared {
     int32_t expert_off[kWave + 1];
     int32_t seg_tot[kPlanWaves][kWave];
     int32_t cnt[kFastMaxT];        // keep_count
-    uint64_t words[kFastMaxT];     // [batch][expert]
-    int32_t prefix[kFastMaxT];     // [batch][expert]
+    union {
+        struct {
+            uint64_t words[kFastMaxT];   // [batch][expert]
+            int32_t prefix[kFastMaxT];   // [batch][expert]
+        };
+        // during the selection, before the dispatch arrays are needed: the candidate
+        // scores, copied in with coalesced loads
+        float stage[kFastMaxT * 3];
+    };
 };
+constexpr int kStageFloats = kFastMaxT * 3;
 
 // Transpose of a 64 x 64 bit matrix held one row per lane: afterwards lane e
 // holds column e (bit t = former bit e of lane t).
@@ -409,17 +417,34 @@ __global__ __launch_bounds__(NT) void plan_fast_kernel(
             const int n0 = min(n_pool, tid * C), n_mine = min(n_pool, n0 + C) - n0;
             const int t_first = n0 / P, j_first = n0 % P;
             uint32_t key[kFastMaxKeys];
+            // A thread's slice is strided in memory (lane stride = C scores), so where the
+            // whole [T,K] score matrix fits the staging area it is copied to LDS with
+            // coalesced loads and the slices are read from there.
+            const bool staged = T * K <= kStageFloats;
+            if (staged) {
+                const int n_all = T * K;
+                if ((n_all & 3) == 0 && (reinterpret_cast<uintptr_t>(topk_s) & 15) == 0) {
+                    const float4* src = reinterpret_cast<const float4*>(topk_s);
+                    float4* dst = reinterpret_cast<float4*>(sh.stage);
+                    for (int i = tid; i < n_all / 4; i += NT) dst[i] = src[i];
+                } else {
+                    for (int i = tid; i < n_all; i += NT) sh.stage[i] = topk_s[i];
+                }
+                __syncthreads();
+            }
             {
                 int t = t_first, j = j_first;
 #pragma unroll
                 for (int q = 0; q < kFastMaxKeys; ++q) {
                     key[q] = 0;
                     if (q < n_mine) {
-                        key[q] = ordered_key(topk_s[static_cast<size_t>(t) * K + Kb + j]);
+                        const size_t at = static_cast<size_t>(t) * K + Kb + j;
+                        key[q] = ordered_key(staged ? sh.stage[at] : topk_s[at]);
                         if (++j == P) { j = 0; ++t; }
                     }
                 }
             }
+            if (staged) __syncthreads();   // the staging area is the dispatch arrays' from here on
             ALLOCMOE_PLAN_STAMP(1);
             // ---- range of the keys
             uint32_t lo = 0xFFFFFFFFu, hi = 0u;
@@ -535,19 +560,44 @@ __global__ __launch_bounds__(NT) void plan_fast_kernel(
     ALLOCMOE_PLAN_STAMP(4);
 
     const int n_batch = (T + kWave - 1) / kWave;
+    // Candidate ids of this wave's batches (lane = token), all loaded up front so that
+    // the loads are in flight together, and kept in registers for both uses below.
+    // Wider candidate rows than kIdsK fall back to loading them where they are used.
+    constexpr int kIdsK = 8;
+    constexpr int kMaxBatches = (NT == 1024 ? kFastMaxT : 1024) / kWave / NW;
+    const bool ids_held = K <= kIdsK;
+    int held[kMaxBatches][kIdsK];
+    if (ids_held) {
+#pragma unroll
+        for (int bi = 0; bi < kMaxBatches; ++bi) {
+            const int t = (wave + bi * NW) * kWave + lane;
+#pragma unroll
+            for (int j = 0; j < kIdsK; ++j)
+                held[bi][j] = (t < T && j < K) ? topk_ids[static_cast<size_t>(t) * K + j] : 0;
+        }
+    }
     // ---- A: ballot words by bit-matrix transpose (lane e ends up with expert e's word)
-    for (int b = wave; b < n_batch; b += NW) {
+#pragma unroll
+    for (int bi = 0; bi < kMaxBatches; ++bi) {
+        const int b = wave + bi * NW;
+        if (b >= n_batch) break;
         const int t = b * kWave + lane;
         uint64_t mine = 0;
         if (t < T) {
             const int kt = min(K, sh.cnt[t]);
-            int ids[kMaxK];   // all loads first, so that they are in flight together
+            if (ids_held) {
 #pragma unroll
-            for (int j = 0; j < kMaxK; ++j)
-                ids[j] = j < K ? topk_ids[static_cast<size_t>(t) * K + j] : 0;
+                for (int j = 0; j < kIdsK; ++j)
+                    if (j < kt) mine |= 1ull << (held[bi][j] & (kWave - 1));
+            } else {
+                int ids[kMaxK];   // all loads first, so that they are in flight together
 #pragma unroll
-            for (int j = 0; j < kMaxK; ++j)
-                if (j < kt) mine |= 1ull << (ids[j] & (kWave - 1));
+                for (int j = 0; j < kMaxK; ++j)
+                    ids[j] = j < K ? topk_ids[static_cast<size_t>(t) * K + j] : 0;
+#pragma unroll
+                for (int j = 0; j < kMaxK; ++j)
+                    if (j < kt) mine |= 1ull << (ids[j] & (kWave - 1));
+            }
         }
         sh.words[b * kWave + lane] = wave_transpose64(mine);
     }
@@ -583,14 +633,22 @@ __global__ __launch_bounds__(NT) void plan_fast_kernel(
     }
     ALLOCMOE_PLAN_STAMP(6);
     // ---- C: place every pair
-    for (int b = wave; b < n_batch; b += NW) {
+#pragma unroll
+    for (int bi = 0; bi < kMaxBatches; ++bi) {
+        const int b = wave + bi * NW;
+        if (b >= n_batch) break;
         const int t = b * kWave + lane;
         if (t >= T) continue;
         const int kt = min(K, sh.cnt[t]);
         const uint64_t below = lanemask_lt();
         int ids[kMaxK];
 #pragma unroll
-        for (int j = 0; j < kMaxK; ++j) ids[j] = j < K ? topk_ids[static_cast<size_t>(t) * K + j] : 0;
+        for (int j = 0; j < kMaxK; ++j) {
+            if (ids_held)
+                ids[j] = j < kIdsK ? held[bi][j < kIdsK ? j : 0] : 0;
+            else
+                ids[j] = j < K ? topk_ids[static_cast<size_t>(t) * K + j] : 0;
+        }
 #pragma unroll
         for (int j = 0; j < kMaxK; ++j) {
             if (j >= K) continue;
