@@ -30,10 +30,14 @@ def parse_args():
     p.add_argument("--steps", type=int, default=200)
     p.add_argument("--warmup", type=int, default=20)
     p.add_argument("--workload", default="decode",
-                   choices=["decode", "prefill", "qwen", "stack"])
+                   choices=["decode", "prefill", "qwen", "olmoe", "stack"])
     p.add_argument("--budget-ratio", type=float, default=0.5,
                    help="layer budget as a fraction of T*K (the metric is quoted at 0.5)")
     p.add_argument("--layers", type=int, default=26, help="layers of the stack workload")
+    p.add_argument("--budgets", default="dirichlet", choices=["dirichlet", "alloc-l"],
+                   help="stack workload: per-layer budgets from the seeded Dirichlet(2) draw "
+                        "(the configuration the metric names) or from Alloc-L's dynamic "
+                        "programme on a seeded synthetic sensitivity matrix (budget = T*K_l)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--copy-probe", action="store_true",
                    help="only run a plain device copy of 1 GiB (calibrates the rocprofv3 "
@@ -51,6 +55,8 @@ def workload_for(name: str, ratio: float):
         w = synth.deepseek_prefill()
     elif name == "qwen":
         w = synth.qwen_moe()
+    elif name == "olmoe":
+        w = synth.olmoe()
     else:
         w = synth.deepseek_stack_layer(budget=0)
     return w.with_(budget=int(round(ratio * w.T * w.K)))
@@ -143,7 +149,12 @@ def main():
     # a model interact only through the budgets Alloc-L gives them).
     layer_cpu = synth.make_layer(w, device="cpu") if on_cpu else None
     if args.workload == "stack":
-        budgets = synth.stack_budgets(args.layers, w.T, w.K, w.K_base, args.budget_ratio)
+        if args.budgets == "alloc-l":
+            S = synth.sensitivity_matrix(args.layers, w.K)
+            K_l, _ = B.allocmoe_alloc_l(S, int(round(args.budget_ratio * args.layers * w.K)))
+            budgets = [w.T * k for k in K_l]
+        else:
+            budgets = synth.stack_budgets(args.layers, w.T, w.K, w.K_base, args.budget_ratio)
         works = [w.with_(budget=b) for b in budgets]
         devs = [DeviceLayer(wl, synth.make_layer(wl, layer=i, device="cuda"))
                 for i, wl in enumerate(works)]

@@ -186,6 +186,21 @@ allocmoe_status allocmoe_moe_forward_timed(const allocmoe_layer_desc *desc, cons
                                            size_t ws_bytes, allocmoe_stream stream,
                                            float *stage_ms);
 
+/* Alloc-L's layer-wise allocation (Section 3.2, Eqs. (3)-(5)), the offline step that
+ * produces the per-layer budgets: given the sensitivity matrix S [L, K_orig] (host,
+ * row-major, S[i*K_orig + k-1] = loss of layer i with k experts per token) and the
+ * global budget B (expert activations per token summed over the layers), writes to
+ * K_out[L] (host) the allocation 1 <= K_i <= K_orig with sum K_i <= B that minimises
+ * sum_i S[i][K_i] (summed in fp64 in layer order), found exactly by the grouped-knapsack
+ * dynamic programme of Eq. (5) with backtracking, O(L * B * K_orig).  Of several
+ * minimisers: the one that spends less, then the one with the smaller K at the deepest
+ * layer, then at the layer before, and so on.  cost_out (host, may be NULL) receives the
+ * minimum.  A layer call then takes budget = T * K_i.  Host-only: touches no device,
+ * uses host heap for the table.  Errors: B < L -> ALLOCMOE_EBUDGET; NaN in S, L < 1,
+ * K_orig < 1 -> ALLOCMOE_EINVAL; L * K_orig > 2^24 -> ALLOCMOE_ESHAPE. */
+allocmoe_status allocmoe_alloc_l(const double *S, int32_t L, int32_t K_orig, int64_t B,
+                                 int32_t *K_out, double *cost_out);
+
 const char *allocmoe_status_string(allocmoe_status status);
 
 #ifdef __cplusplus

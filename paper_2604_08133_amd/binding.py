@@ -22,7 +22,7 @@ EXPORTS = [
     "allocmoe_workspace_bytes", "allocmoe_workspace_layout", "allocmoe_packed_bytes",
     "allocmoe_pack_weights", "allocmoe_route", "allocmoe_route_from_scores",
     "allocmoe_dispatch", "allocmoe_moe_forward", "allocmoe_moe_forward_timed",
-    "allocmoe_status_string",
+    "allocmoe_alloc_l", "allocmoe_status_string",
 ]
 STAGES = ["route", "plan", "ffn1", "ffn2", "combine"]
 
@@ -181,6 +181,20 @@ def allocmoe_moe_forward_timed(desc: LayerDesc, X, w: Weights, Y, ws: torch.Tens
                                              ctypes.c_size_t(ws.numel() * ws.element_size()),
                                              _stream(stream), ms), "allocmoe_moe_forward_timed")
     return list(ms)
+
+
+def allocmoe_alloc_l(S, B: int):
+    """S: [L, K_orig] rows of float (any nested sequence or tensor, host).  Returns
+    (K, cost): the allocation as a list of L ints and its total sensitivity."""
+    rows = [[float(v) for v in row] for row in S]
+    L, K_orig = len(rows), len(rows[0])
+    flat = (ctypes.c_double * (L * K_orig))(*[v for row in rows for v in row])
+    out = (ctypes.c_int32 * L)()
+    cost = ctypes.c_double(0.0)
+    _check(load().allocmoe_alloc_l(flat, ctypes.c_int32(L), ctypes.c_int32(K_orig),
+                                   ctypes.c_int64(int(B)), out, ctypes.byref(cost)),
+           "allocmoe_alloc_l")
+    return list(out), cost.value
 
 
 # ------------------------------------------------ conveniences for tests/bench

@@ -68,6 +68,12 @@ def qwen_moe(budget: int = 4096, T: int = 2048) -> Workload:
                     shared_gate=True)
 
 
+def olmoe(budget: int = 8192, T: int = 2048) -> Workload:
+    """OLMoE-1B-7B-shaped layer (Table 1: 64 experts, Top-8, no shared expert)."""
+    return Workload("olmoe_1b_7b", T=T, d=2048, E=64, I=1024, K=8, K_base=1, budget=budget,
+                    dtype="bf16")
+
+
 def deepseek_stack_layer(budget: int, T: int = 8192) -> Workload:
     return Workload("deepseek_v2_lite_stack_layer", T=T, d=2048, E=64, I=1408, K=6,
                     K_base=1, budget=budget, dtype="bf16", I_shared=2816,
@@ -167,3 +173,24 @@ def stack_budgets(L: int, T: int, K: int, K_base: int, ratio: float,
             diff -= step * take
         i = (i + 1) % L
     return b
+
+
+def sensitivity_matrix(L: int, K: int, seed: int = BASE_SEED) -> list:
+    """A seeded stand-in for the sensitivity matrix S [L, K] that Alloc-L profiles on a
+    calibration set (Section 3.2, Algorithm 1; neither the models nor the data are
+    available here): row i is the loss of layer i with k = 1..K experts per token,
+    decreasing in k with diminishing returns, the scale of the drop differing from
+    layer to layer (shallow and deep layers are more sensitive in the paper's figures)."""
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed * 1000003 + _TENSOR_IDS["budget"] * 1009 + 77)
+    u = torch.rand((L, K), generator=g, dtype=torch.float64)
+    rows = []
+    for i in range(L):
+        depth = abs(2.0 * i / max(L - 1, 1) - 1.0)           # 1 at both ends, 0 in the middle
+        scale = 0.5 + 1.5 * depth + float(u[i, 0])
+        gains = sorted((float(v) * scale / (j + 1) for j, v in enumerate(u[i, 1:])), reverse=True)
+        row = [10.0 + scale * 2.0]
+        for gain in gains:
+            row.append(row[-1] - gain)
+        rows.append(row)
+    return rows

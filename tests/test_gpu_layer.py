@@ -111,6 +111,16 @@ def test_qwen_shape_reduced_tokens():
     check_layer(w, layer)
 
 
+def test_olmoe_shape_no_shared_expert():
+    # Top-8 of 64 experts, no shared expert: reduced token count, tile-kernel path
+    w = synth.olmoe(budget=4 * 256, T=256)
+    layer = synth.make_layer(w)
+    tokens = sample_tokens(w.T, 24, seed=8)           # outputs checked on a sample, indices on all
+    dev = check_layer(w, layer, tokens=tokens)                        # streaming kernel
+    check_layer(w, layer, budget=8 * 256, tokens=tokens, dev=dev)     # original Top-8, tile kernel
+    check_layer(w, layer, budget=256, K_base=1, tokens=tokens, dev=dev)   # Top-1 only
+
+
 @pytest.fixture(scope="module")
 def deepseek_big():
     """DeepSeek-V2-Lite-shaped weights shared by the full-size tests."""
