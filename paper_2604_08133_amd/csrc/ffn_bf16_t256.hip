@@ -107,18 +107,26 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
         for (int i = 0; i < NRB; ++i)
             load_rows_to_lds(arow[i] + s * (kStepK / 8), lds_wave + slot * kSlotBytes + i * 4096);
     };
-    const int KQ = 4 * KT;   // k16 steps in total
     bf16x8 breg[kBRing][2];
+    // Weight fragments come through buffer loads: a scalar descriptor per stream
+    // (base, size), the lane's offset in a VGPR and the k16 step's offset in an SGPR,
+    // so a load costs no address arithmetic on the vector unit; a step past the end
+    // of the stream reads zeros instead of faulting.  Weights that no other tile
+    // reads are marked non-temporal: they need not displace what the caches hold
+    // for tiles that share theirs.
+    typedef __attribute__((__vector_size__(4 * sizeof(int)))) int i32x4;
+    const int stream_bytes = KT * kStepK * 32 * 2;
+    const __amdgpu_buffer_rsrc_t rs0 = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16x8*>(b0), 0, stream_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs1 = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16x8*>(b1), 0, stream_bytes, 0x00020000);
+    const int lane_off = lane * 16;
     auto load_b = [&](int q, int r) {
-        // weights that no other tile reads are marked non-temporal: they need not
-        // displace what the caches hold for tiles that share theirs
-        if (STREAM_ONCE) {
-            breg[r][0] = __builtin_nontemporal_load(b0 + static_cast<size_t>(q) * kWave);
-            breg[r][1] = __builtin_nontemporal_load(b1 + static_cast<size_t>(q) * kWave);
-        } else {
-            breg[r][0] = b0[static_cast<size_t>(q) * kWave];
-            breg[r][1] = b1[static_cast<size_t>(q) * kWave];
-        }
+        constexpr int kAux = STREAM_ONCE ? 2 : 0;   // nt
+        const i32x4 v0 = __builtin_amdgcn_raw_buffer_load_b128(rs0, lane_off, q * 1024, kAux);
+        const i32x4 v1 = __builtin_amdgcn_raw_buffer_load_b128(rs1, lane_off, q * 1024, kAux);
+        breg[r][0] = __builtin_bit_cast(bf16x8, v0);
+        breg[r][1] = __builtin_bit_cast(bf16x8, v1);
     };
     // A operand of row block i, k16 chunk kc of a slot: lane l reads row m = l%32 of
     // the block, 16-byte chunk c = 2 kc + l/32 of that row, stored at position
@@ -182,7 +190,7 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
             }
             __builtin_amdgcn_sched_group_barrier(0x008, NRB, 0);     // the remaining MFMAs
             __builtin_amdgcn_sched_barrier(0);
-            load_b(min(4 * s2 + u + kBRing, KQ - 1), u);
+            load_b(4 * s2 + u + kBRing, u);
             if (kc == 2) {
                 // this wave's part of the next slot has landed; after the barrier
                 // everybody's has, and everybody is done with the slot before this one
@@ -291,7 +299,7 @@ __global__ __launch_bounds__(kWaves* kWave, 1) void ffn_bf16_t256_kernel(StreamG
         rows = min(kRows, M_dense - row0);
         only_tile = M_dense <= kRows;
     }
-    const int lane = lane_id(), wave = threadIdx.x / kWave;
+    const int lane = lane_id(), wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int n_rb = (rows + 31) / 32;   // 32-row blocks that hold real rows
     const int KT = Kd / kStepK;
 #ifdef ALLOCMOE_TRACE
@@ -303,8 +311,9 @@ __global__ __launch_bounds__(kWaves* kWave, 1) void ffn_bf16_t256_kernel(StreamG
     const size_t stream_elems = static_cast<size_t>(Kd) * 32;
     const size_t sidx = SWIGLU ? static_cast<size_t>(4 * nt + wave) * 2
                                : static_cast<size_t>(8 * nt + 2 * wave);
+    // (wave-uniform pointers: the loads take a scalar base and the lane's offset)
     const bf16x8* b0 = reinterpret_cast<const bf16x8*>(
-                           Bp + static_cast<size_t>(e) * g.group_stride + sidx * stream_elems) + lane;
+        Bp + static_cast<size_t>(e) * g.group_stride + sidx * stream_elems);
     const bf16x8* b1 = b0 + stream_elems / 8;
 
 #define ALLOCMOE_T256_CASE(n)                                                                       \
