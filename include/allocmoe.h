@@ -186,6 +186,34 @@ allocmoe_status allocmoe_moe_forward_timed(const allocmoe_layer_desc *desc, cons
                                            size_t ws_bytes, allocmoe_stream stream,
                                            float *stage_ms);
 
+/* Summary numbers of allocmoe_routing_stats (device memory, 5 floats in this order). */
+typedef struct {
+    float spearman_load;   /* Spearman rank correlation of the per-expert loads, original vs budgeted */
+    float entropy_orig;    /* normalised entropy of the score-weighted load distribution, original */
+    float entropy_kept;    /* the same under the budgeted routing                                    */
+    float js_divergence;   /* Jensen-Shannon divergence between the two distributions (nats)         */
+    float spearman_tokens; /* Spearman correlation: token routing entropy vs experts kept            */
+} allocmoe_routing_metrics;
+
+/* Routing analytics of one layer (Section 5, "Analysis of Expert Load Balance" and
+ * "Analysis of Budget Allocation in Alloc-L and Alloc-T"), from a routing result as
+ * allocmoe_route leaves it: scores f32 [T,E], topk_ids i32 [T,K], topk_s f32 [T,K],
+ * keep_count i32 [T] (all device).  "Original" routing = all K candidates of every
+ * token, budgeted = the first keep_count[t].  Outputs (device): load_orig, load_kept
+ * i32 [E] (pairs per expert), wload_orig, wload_kept f32 [E] (sum of their routing
+ * scores), token_entropy f32 [T] (H_t = -sum_e s ln s over all E experts), metrics.
+ * Entropies are normalised by ln E, logarithms are natural, rank correlations use
+ * average ranks for ties and are 0 when one side is constant (the paper names the
+ * statistics only).  ws: device scratch of at least 4*T bytes, 256-byte aligned.
+ * Deterministic: no floating-point atomics; the rank correlations come from exact
+ * integer sums.  Only desc->T, E, K are used (after the usual validation). */
+allocmoe_status allocmoe_routing_stats(const allocmoe_layer_desc *desc, const float *scores,
+                                       const int32_t *topk_ids, const float *topk_s,
+                                       const int32_t *keep_count, int32_t *load_orig,
+                                       int32_t *load_kept, float *wload_orig, float *wload_kept,
+                                       float *token_entropy, allocmoe_routing_metrics *metrics,
+                                       void *ws, size_t ws_bytes, allocmoe_stream stream);
+
 /* Alloc-L's layer-wise allocation (Section 3.2, Eqs. (3)-(5)), the offline step that
  * produces the per-layer budgets: given the sensitivity matrix S [L, K_orig] (host,
  * row-major, S[i*K_orig + k-1] = loss of layer i with k experts per token) and the

@@ -22,7 +22,7 @@ EXPORTS = [
     "allocmoe_workspace_bytes", "allocmoe_workspace_layout", "allocmoe_packed_bytes",
     "allocmoe_pack_weights", "allocmoe_route", "allocmoe_route_from_scores",
     "allocmoe_dispatch", "allocmoe_moe_forward", "allocmoe_moe_forward_timed",
-    "allocmoe_alloc_l", "allocmoe_status_string",
+    "allocmoe_alloc_l", "allocmoe_routing_stats", "allocmoe_status_string",
 ]
 STAGES = ["route", "plan", "ffn1", "ffn2", "combine"]
 
@@ -181,6 +181,29 @@ def allocmoe_moe_forward_timed(desc: LayerDesc, X, w: Weights, Y, ws: torch.Tens
                                              ctypes.c_size_t(ws.numel() * ws.element_size()),
                                              _stream(stream), ms), "allocmoe_moe_forward_timed")
     return list(ms)
+
+
+METRICS = ["spearman_load", "entropy_orig", "entropy_kept", "js_divergence", "spearman_tokens"]
+
+
+def allocmoe_routing_stats(desc: LayerDesc, scores, topk_ids, topk_s, keep_count, stream=None) -> dict:
+    """Allocates the outputs (torch, on the inputs' device) and returns them by name;
+    'metrics' is a float tensor of len(METRICS)."""
+    dev = scores.device
+    E, T = int(desc.E), int(desc.T)
+    out = dict(load_orig=torch.empty(E, dtype=torch.int32, device=dev),
+               load_kept=torch.empty(E, dtype=torch.int32, device=dev),
+               wload_orig=torch.empty(E, dtype=torch.float32, device=dev),
+               wload_kept=torch.empty(E, dtype=torch.float32, device=dev),
+               token_entropy=torch.empty(T, dtype=torch.float32, device=dev),
+               metrics=torch.empty(len(METRICS), dtype=torch.float32, device=dev))
+    ws = torch.empty(max(256, 4 * T), dtype=torch.uint8, device=dev)
+    _check(load().allocmoe_routing_stats(
+        ctypes.byref(desc), _ptr(scores), _ptr(topk_ids), _ptr(topk_s), _ptr(keep_count),
+        _ptr(out["load_orig"]), _ptr(out["load_kept"]), _ptr(out["wload_orig"]),
+        _ptr(out["wload_kept"]), _ptr(out["token_entropy"]), _ptr(out["metrics"]), _ptr(ws),
+        ctypes.c_size_t(ws.numel()), _stream(stream)), "allocmoe_routing_stats")
+    return out
 
 
 def allocmoe_alloc_l(S, B: int):

@@ -240,6 +240,27 @@ allocmoe_status allocmoe_dispatch(const allocmoe_layer_desc* desc, const int32_t
     return ALLOCMOE_OK;
 }
 
+allocmoe_status allocmoe_routing_stats(const allocmoe_layer_desc* desc, const float* scores,
+                                       const int32_t* topk_ids, const float* topk_s,
+                                       const int32_t* keep_count, int32_t* load_orig,
+                                       int32_t* load_kept, float* wload_orig, float* wload_kept,
+                                       float* token_entropy, allocmoe_routing_metrics* metrics,
+                                       void* ws, size_t ws_bytes, allocmoe_stream stream_) {
+    const allocmoe_status st = check_desc(desc);
+    if (st != ALLOCMOE_OK) return st;
+    if (!scores || !topk_ids || !topk_s || !keep_count || !load_orig || !load_kept ||
+        !wload_orig || !wload_kept || !token_entropy || !metrics)
+        return ALLOCMOE_EINVAL;
+    if (ws == nullptr || ws_bytes < static_cast<size_t>(desc->T) * 4 || !aligned(ws, kAlign))
+        return ALLOCMOE_EWORKSPACE;
+    ALLOCMOE_TRY(launch_routing_stats(scores, topk_ids, topk_s, keep_count, desc->T, desc->E,
+                                      desc->K, load_orig, load_kept, wload_orig, wload_kept,
+                                      token_entropy, static_cast<int32_t*>(ws),
+                                      reinterpret_cast<float*>(metrics),
+                                      static_cast<hipStream_t>(stream_)));
+    return ALLOCMOE_OK;
+}
+
 }  // extern "C"
 
 namespace {

@@ -94,6 +94,13 @@ hipError_t launch_pack_b(const void* W, int G, int Kd, int N, void* out,
                          size_t group_stride_elems, size_t nblock_stride_elems,
                          size_t base_off_elems, hipStream_t stream);
 
+// ---- stats.hip : routing analytics; metrics: 5 floats (see allocmoe_routing_metrics)
+hipError_t launch_routing_stats(const float* scores, const int32_t* topk_ids, const float* topk_s,
+                                const int32_t* keep_count, int T, int E, int K,
+                                int32_t* load_orig, int32_t* load_kept, float* wload_orig,
+                                float* wload_kept, float* token_entropy, int32_t* entropy_rank2,
+                                float* metrics, hipStream_t stream);
+
 // ---- combine.hip : y_t = sum_j s[t,j] O[inv_row[t,j]] + g_t Os[t]
 hipError_t launch_combine(int out_dtype, const float* O, const float* Os, const int32_t* inv_row,
                           const float* topk_s, const int32_t* keep_count, const float* sgate,
