@@ -38,6 +38,9 @@ def parse_args():
                    help="stack workload: per-layer budgets from the seeded Dirichlet(2) draw "
                         "(the configuration the metric names) or from Alloc-L's dynamic "
                         "programme on a seeded synthetic sensitivity matrix (budget = T*K_l)")
+    p.add_argument("--selector", default="score", choices=["score", "top-p", "relative"],
+                   help="token-level selector: Alloc-T (the metric's) or one of the calibrated "
+                        "baselines of Appendix A.1, at the same budget")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--copy-probe", action="store_true",
                    help="only run a plain device copy of 1 GiB (calibrates the rocprofv3 "
@@ -161,7 +164,8 @@ def main():
     else:
         works = [w]
         devs = [DeviceLayer(w, layer_cpu if on_cpu else synth.make_layer(w, device="cuda"))]
-    descs = [dv.desc() for dv in devs]
+    selector = {"score": B.SELECT_SCORE, "top-p": B.SELECT_TOP_P, "relative": B.SELECT_RELATIVE}[args.selector]
+    descs = [dv.desc(selector=selector) for dv in devs]
     ws = torch.empty(max(B.allocmoe_workspace_bytes(dc) for dc in descs), dtype=torch.uint8,
                      device="cuda")
     Y = torch.empty((w.T, w.d), dtype=devs[0].dtype, device="cuda")
@@ -251,7 +255,7 @@ def main():
         "config": {"workload": w.name + (f"_x{nL}_layers" if nL > 1 else ""), "T": w.T, "d": w.d,
                    "E": w.E, "I": w.I, "K": w.K, "K_base": w.K_base,
                    "budget": [wl.budget for wl in works] if nL > 1 else w.budget,
-                   "budget_ratio": args.budget_ratio, "I_shared": w.I_shared,
+                   "budget_ratio": args.budget_ratio, "I_shared": w.I_shared, "selector": args.selector,
                    "weights": "re-tiled once by allocmoe_pack_weights, outside the timed region"},
         "roofline": roof,
         "step": step_info,

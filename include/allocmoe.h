@@ -69,8 +69,28 @@ typedef struct {
     int32_t I_shared;     /* 0 = no shared expert; else its (fused) intermediate width  */
     int32_t shared_gate;  /* 0: y += Shared(x);  1: y += sigmoid(x . w_sg) * Shared(x)  */
     int32_t dtype;        /* allocmoe_dtype of X, Y and every weight matrix             */
-    int32_t flags;        /* reserved, must be 0                                        */
+    int32_t flags;        /* allocmoe_selector; every other bit must be 0               */
 } allocmoe_layer_desc;
+
+/* Token-level selector (desc->flags).  All of them keep every token's first K_base
+ * candidates and then the B - T*K_base pool entries with the largest key (ties: lower
+ * token, then lower rank), i.e. they spend exactly the layer budget; they differ in
+ * the key of candidate j of token t (formed in fp32, non-increasing along the sorted
+ * row, so a token's kept candidates are a prefix):
+ *   SCORE    s[t,j]                              Alloc-T (Section 3.3)
+ *   TOP_P    -(s[t,0] + ... + s[t,j-1])          Top-P routing (Dynamic-MoE baseline,
+ *            Appendix A.1): kept while the mass before j is below p, the threshold p
+ *            being the one that meets the budget on this batch
+ *   RELATIVE s[t,j] / s[t,0] (0 if s[t,0] <= 0)  expert skipping relative to the Top-1
+ *            score (NAEE baseline extended to Top-K, Appendix A.1): kept iff >= beta,
+ *            beta being the one that meets the budget on this batch
+ * Uniform Top-K_l is SCORE with K_base = K_l and budget = T*K_l.  TOP_P and RELATIVE
+ * need T*K*4 bytes of device scratch in the calls that take `ws`. */
+typedef enum {
+    ALLOCMOE_SELECT_SCORE = 0,
+    ALLOCMOE_SELECT_TOP_P = 1,
+    ALLOCMOE_SELECT_RELATIVE = 2
+} allocmoe_selector;
 
 /* Weights, all device pointers, read-only.  gate_bias (fp32 [E], added to the
  * logits before the softmax) and the shared-expert fields may be NULL.
@@ -99,6 +119,7 @@ typedef struct {
     size_t expert_offsets, row_token, row_rank, inv_row;
     size_t H, Hs, O, Os;
     size_t scratch; /* selection/dispatch scratch and tile map */
+    size_t sel_keys; /* f32 [T,K] selector keys (TOP_P / RELATIVE only)                  */
     size_t total;   /* == allocmoe_workspace_bytes                                      */
 } allocmoe_ws_layout;
 

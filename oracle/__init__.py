@@ -167,14 +167,19 @@ def route(layer: dict, K: int):
 
 
 def forward(layer: dict, K: int, K_base: int, budget: int, scores=None,
-            tokens: Optional[Sequence[int]] = None) -> dict:
+            tokens: Optional[Sequence[int]] = None, selector: int = 0) -> dict:
     """Whole layer by the paper's definitions.  If `scores` is given the
-    selection starts from it (the split point for bit-exact index parity)."""
+    selection starts from it (the split point for bit-exact index parity).
+    selector: 0 = Alloc-T, otherwise a calibrated baseline of oracle/selectors.py."""
     sg = shared_gate(layer["X"], layer["w_sg"]) if layer.get("w_sg") is not None else None
     if scores is None:
         scores = softmax(gate_logits(layer["X"], layer["Wg"], layer.get("bias")))
     ids, s = topk(scores, K)
-    kept, cnt = alloc_t(s, K_base, budget)
+    if selector == 0:
+        kept, cnt = alloc_t(s, K_base, budget)
+    else:
+        from . import selectors
+        kept, cnt = selectors.select(s, selector, K_base, budget)
     offs, row_token, row_rank, inv_row = dispatch(ids, kept, layer["W1"].shape[0])
     Y = moe_eq2(layer, ids, s, kept, sg, dense=False, tokens=tokens)
     return dict(scores=scores, topk_ids=ids, topk_s=s, kept=kept, keep_count=cnt,

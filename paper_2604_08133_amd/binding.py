@@ -43,7 +43,8 @@ class Weights(ctypes.Structure):
 class WsLayout(ctypes.Structure):
     _fields_ = [(n, ctypes.c_size_t) for n in
                 ("scores", "topk_ids", "topk_s", "keep_count", "shared_gate", "expert_offsets",
-                 "row_token", "row_rank", "inv_row", "H", "Hs", "O", "Os", "scratch", "total")]
+                 "row_token", "row_rank", "inv_row", "H", "Hs", "O", "Os", "scratch", "sel_keys",
+                 "total")]
 
 
 class AllocMoEError(RuntimeError):
@@ -96,9 +97,14 @@ def _stream(stream) -> ctypes.c_void_p:
     return ctypes.c_void_p(stream.cuda_stream)
 
 
-def make_desc(T, d, E, I, K, K_base, budget, dtype, I_shared=0, shared_gate=False) -> LayerDesc:
+SELECT_SCORE, SELECT_TOP_P, SELECT_RELATIVE = 0, 1, 2
+
+
+def make_desc(T, d, E, I, K, K_base, budget, dtype, I_shared=0, shared_gate=False,
+              selector=SELECT_SCORE) -> LayerDesc:
     code = {"f32": F32, "bf16": BF16, torch.float32: F32, torch.bfloat16: BF16}.get(dtype, dtype)
-    return LayerDesc(T, d, E, I, K, K_base, budget, I_shared, 1 if shared_gate else 0, code, 0)
+    return LayerDesc(T, d, E, I, K, K_base, budget, I_shared, 1 if shared_gate else 0, code,
+                     int(selector))
 
 
 def make_weights(Wg=None, gate_bias=None, W1=None, W3=None, W2=None, Ws1=None, Ws3=None,

@@ -42,7 +42,7 @@ Scratch scratch_of(const allocmoe_layer_desc* d) {
 allocmoe_status check_desc(const allocmoe_layer_desc* d) {
     if (d == nullptr) return ALLOCMOE_EINVAL;
     if (d->dtype != ALLOCMOE_F32 && d->dtype != ALLOCMOE_BF16) return ALLOCMOE_EINVAL;
-    if (d->flags != 0) return ALLOCMOE_EINVAL;
+    if (d->flags < ALLOCMOE_SELECT_SCORE || d->flags > ALLOCMOE_SELECT_RELATIVE) return ALLOCMOE_EINVAL;
     if (d->T < 1 || d->d < 1 || d->E < 1 || d->I < 1 || d->K < 1) return ALLOCMOE_EINVAL;
     if (d->K_base < 0 || d->K_base > d->K || d->K > d->E) return ALLOCMOE_EINVAL;
     if (d->I_shared < 0 || (d->shared_gate != 0 && d->shared_gate != 1)) return ALLOCMOE_EINVAL;
@@ -69,6 +69,7 @@ allocmoe_status layout_of(const allocmoe_layer_desc* d, allocmoe_ws_layout* L) {
         return at;
     };
     L->scratch = take(scratch_of(d).bytes);
+    L->sel_keys = take(d->flags != ALLOCMOE_SELECT_SCORE ? T * K * 4 : 0);
     L->scores = take(T * E * 4);
     L->topk_ids = take(T * K * 4);
     L->topk_s = take(T * K * 4);
@@ -189,8 +190,11 @@ allocmoe_status allocmoe_route(const allocmoe_layer_desc* desc, const void* X,
     const allocmoe_status st = check_desc(desc);
     if (st != ALLOCMOE_OK) return st;
     if (!X || !w || !w->Wg || !topk_ids || !topk_s || !keep_count) return ALLOCMOE_EINVAL;
-    (void)ws;
-    (void)ws_bytes;   // the selection runs out of LDS; no device scratch needed here
+    // the selection runs out of LDS; only the selector keys need device scratch
+    const bool keyed = desc->flags != ALLOCMOE_SELECT_SCORE;
+    const size_t key_bytes = static_cast<size_t>(desc->T) * desc->K * 4;
+    if (keyed && (ws == nullptr || ws_bytes < key_bytes || !aligned(ws, kAlign)))
+        return ALLOCMOE_EWORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     if (desc->dtype == ALLOCMOE_BF16 && w->packed != nullptr) {
         if (!aligned(w->packed, kAlign) || !aligned(X, 16)) return ALLOCMOE_EINVAL;
@@ -201,7 +205,13 @@ allocmoe_status allocmoe_route(const allocmoe_layer_desc* desc, const void* X,
         ALLOCMOE_TRY(launch_route(desc->dtype, X, w->Wg, w->gate_bias, nullptr, desc->T, desc->d,
                                   desc->E, desc->K, scores, topk_ids, topk_s, nullptr, stream));
     }
-    ALLOCMOE_TRY(launch_select(topk_s, desc->T, desc->K, desc->K_base, desc->budget, keep_count,
+    const float* keys = topk_s;
+    if (keyed) {
+        ALLOCMOE_TRY(launch_selector_keys(topk_s, desc->T, desc->K, desc->flags,
+                                          static_cast<float*>(ws), stream));
+        keys = static_cast<const float*>(ws);
+    }
+    ALLOCMOE_TRY(launch_select(keys, desc->T, desc->K, desc->K_base, desc->budget, keep_count,
                                stream));
     return ALLOCMOE_OK;
 }
@@ -213,11 +223,19 @@ allocmoe_status allocmoe_route_from_scores(const allocmoe_layer_desc* desc, cons
     const allocmoe_status st = check_desc(desc);
     if (st != ALLOCMOE_OK) return st;
     if (!scores || !topk_ids || !topk_s || !keep_count) return ALLOCMOE_EINVAL;
-    (void)ws;
-    (void)ws_bytes;
+    const bool keyed = desc->flags != ALLOCMOE_SELECT_SCORE;
+    const size_t key_bytes = static_cast<size_t>(desc->T) * desc->K * 4;
+    if (keyed && (ws == nullptr || ws_bytes < key_bytes || !aligned(ws, kAlign)))
+        return ALLOCMOE_EWORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     ALLOCMOE_TRY(launch_topk_from_scores(scores, desc->T, desc->E, desc->K, topk_ids, topk_s, stream));
-    ALLOCMOE_TRY(launch_select(topk_s, desc->T, desc->K, desc->K_base, desc->budget, keep_count,
+    const float* keys = topk_s;
+    if (keyed) {
+        ALLOCMOE_TRY(launch_selector_keys(topk_s, desc->T, desc->K, desc->flags,
+                                          static_cast<float*>(ws), stream));
+        keys = static_cast<const float*>(ws);
+    }
+    ALLOCMOE_TRY(launch_select(keys, desc->T, desc->K, desc->K_base, desc->budget, keep_count,
                                stream));
     return ALLOCMOE_OK;
 }
@@ -406,7 +424,13 @@ allocmoe_status forward_impl(const allocmoe_layer_desc* desc, const void* X,
     }
     // steps 3-4: Alloc-T selection, dispatch, tile map
     ALLOCMOE_MARK(ALLOCMOE_STAGE_PLAN);
-    ALLOCMOE_TRY(launch_plan(topk_s, topk_ids, T, K, desc->K_base, B, E, keep_count,
+    const float* sel_keys = topk_s;   // Alloc-T selects on the scores themselves
+    if (desc->flags != ALLOCMOE_SELECT_SCORE) {
+        ALLOCMOE_TRY(launch_selector_keys(topk_s, T, K, desc->flags, at<float>(base, L.sel_keys),
+                                          stream));
+        sel_keys = at<float>(base, L.sel_keys);
+    }
+    ALLOCMOE_TRY(launch_plan(sel_keys, topk_ids, T, K, desc->K_base, B, E, keep_count,
                              expert_offsets, row_token, row_rank, inv_row,
                              at<uint64_t>(scr, s.words), at<int32_t>(scr, s.prefix), bm, tile_info,
                              stream));

@@ -39,6 +39,10 @@ hipError_t launch_topk_from_scores(const float* scores, int T, int E, int K, int
                                    float* topk_s, hipStream_t stream);
 
 // ---- plan.hip
+// keys of the alternative selectors (mode: allocmoe_selector, 1 or 2) from the sorted
+// candidate scores [T,K]
+hipError_t launch_selector_keys(const float* topk_s, int T, int K, int mode, float* keys,
+                                hipStream_t stream);
 hipError_t launch_select(const float* topk_s, int T, int K, int Kb, int64_t B,
                          int32_t* keep_count, hipStream_t stream);
 hipError_t launch_dispatch(const int32_t* topk_ids, const int32_t* keep_count, int T, int K,

@@ -718,6 +718,35 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
     if (tile_info != nullptr) tilemap_phase(sh, E, bm, tile_info);
 }
 
+// Keys of the calibrated baseline selectors (include/allocmoe.h, allocmoe_selector),
+// one thread per token, fp32: mode 1 -> minus the score mass before candidate j
+// (sequential adds), mode 2 -> s[t,j] / s[t,0] (correctly rounded division).
+__global__ __launch_bounds__(256) void selector_keys_kernel(const float* __restrict__ topk_s, int T,
+                                                            int K, int mode,
+                                                            float* __restrict__ keys) {
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= T) return;
+    const float* s = topk_s + static_cast<size_t>(t) * K;
+    float* k = keys + static_cast<size_t>(t) * K;
+    if (mode == 1) {
+        float mass = 0.f;
+        for (int j = 0; j < K; ++j) {
+            k[j] = -mass;
+            mass = __fadd_rn(mass, s[j]);
+        }
+    } else {
+        const float top = s[0];
+        for (int j = 0; j < K; ++j) k[j] = top > 0.f ? __fdiv_rn(s[j], top) : 0.f;
+    }
+}
+
+hipError_t launch_selector_keys(const float* topk_s, int T, int K, int mode, float* keys,
+                                hipStream_t stream) {
+    hipLaunchKernelGGL(selector_keys_kernel, dim3((T + 255) / 256), dim3(256), 0, stream, topk_s, T,
+                       K, mode, keys);
+    return hipGetLastError();
+}
+
 hipError_t launch_select(const float* topk_s, int T, int K, int Kb, int64_t B,
                          int32_t* keep_count, hipStream_t stream) {
     const int nt = fast_path_threads(T, K, Kb);

@@ -42,11 +42,12 @@ class DeviceLayer:
         self._ws: Optional[torch.Tensor] = None
         self._ws_budget = None
 
-    def desc(self, budget: Optional[int] = None, K_base: Optional[int] = None) -> B.LayerDesc:
+    def desc(self, budget: Optional[int] = None, K_base: Optional[int] = None,
+             selector: int = B.SELECT_SCORE) -> B.LayerDesc:
         w = self.w
         return B.make_desc(w.T, w.d, w.E, w.I, w.K, w.K_base if K_base is None else K_base,
                            w.budget if budget is None else budget, w.dtype, w.I_shared,
-                           w.shared_gate)
+                           w.shared_gate, selector=selector)
 
     def workspace(self, desc: B.LayerDesc) -> torch.Tensor:
         need = B.allocmoe_workspace_bytes(desc)
