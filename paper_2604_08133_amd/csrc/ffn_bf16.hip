@@ -142,7 +142,7 @@ __global__ __launch_bounds__(kStreamWaves* kWave) void ffn_bf16_stream_kernel(St
         if (mr < rows) {
             const size_t off = static_cast<size_t>(row0 + mr) * ldc + n;
             if (SWIGLU)
-                static_cast<bf16_t*>(Cv)[off] = f32_to_bf16((v1 / (1.f + __expf(-v1))) * v3);
+                static_cast<bf16_t*>(Cv)[off] = f32_to_bf16(v1 * v3 * __builtin_amdgcn_rcpf(1.f + __expf(-v1)));
             else
                 static_cast<float*>(Cv)[off] = v1;
         }

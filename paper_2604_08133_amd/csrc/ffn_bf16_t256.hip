@@ -43,7 +43,6 @@ constexpr int kSlotBytes = kRows * kStepK * 2;
 constexpr int kXcds = 8;                // accelerator dies (one L2 each) of an MI355X
 constexpr int kBRing = 8;               // k16 steps of weight fragments held in registers
 
-__device__ __forceinline__ int acc_row(int r, int l) { return 8 * (r / 4) + 4 * (l / 32) + (r % 4); }
 
 // 8 rows x 128 B of activations, global -> LDS directly: lane l's 16 bytes land
 // at lds_addr + 16 l (M0 holds the wave-uniform LDS base; one idle state between
@@ -76,11 +75,23 @@ __device__ __forceinline__ void wait_vmcnt_le() {
     __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
+#ifdef ALLOCMOE_TRACE
+__device__ long long t256_phase[2][1 << 14][4];
+#define ALLOCMOE_T256_PHASE(i)                                                              \
+    do {                                                                                    \
+        if (threadIdx.x == 0 && blockIdx.x < (1 << 14))                                     \
+            t256_phase[SWIGLU ? 0 : 1][blockIdx.x][i] = clock64();                           \
+    } while (0)
+#else
+#define ALLOCMOE_T256_PHASE(i)
+#endif
+
 template <bool SWIGLU, int NRB, bool STREAM_ONCE>
 __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda,
                                           const int32_t* row_map, const bf16x8* b0,
                                           const bf16x8* b1, int KT, int wave, int lane, int row0,
                                           int rows, int nt, void* C, int ldc) {
+    ALLOCMOE_T256_PHASE(0);
     f32x16 acc[NRB][2];
 #pragma unroll
     for (int i = 0; i < NRB; ++i)
@@ -140,11 +151,16 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
 #pragma unroll
         for (int i = 0; i < NRB; ++i) a[i] = *reinterpret_cast<const bf16x8*>(base + i * (32 * 128));
     };
+    // The weight fragment is the first MFMA operand and the activation fragment
+    // the second, i.e. the unit forms the transposed 32x32 block: register r of lane
+    // l then holds the output of token row l%32 at column 8*(r/4) + 4*(l/32) + r%4,
+    // four consecutive columns per register quad, which the epilogue stores as one
+    // 8- or 16-byte word.
     auto multiply = [&](const bf16x8 (&a)[NRB], const bf16x8 (&b)[2]) {
 #pragma unroll
         for (int i = 0; i < NRB; ++i) {
-            acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[0], acc[i][0], 0, 0, 0);
-            acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[1], acc[i][1], 0, 0, 0);
+            acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[0], a[i], acc[i][0], 0, 0, 0);
+            acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[1], a[i], acc[i][1], 0, 0, 0);
         }
     };
 
@@ -170,6 +186,7 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
     wg_barrier_nofence();
     bf16x8 af[2][NRB];
     read_a(0, 0, af[0]);
+    ALLOCMOE_T256_PHASE(1);
 
     for (int s2 = 0; s2 < KT; s2 += 2) {
 #pragma unroll
@@ -202,26 +219,74 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
     }
     __builtin_amdgcn_sched_barrier(0);
     wait_vmcnt_le<0>();   // the surplus loads have landed before registers and LDS are reused
+    ALLOCMOE_T256_PHASE(2);
 
-    // epilogue: lane l, register r -> row 8*(r/4) + 4*(l/32) + r%4, column l%32
-    const int col = lane % 32;
+    // epilogue: lane l owns token row l%32 of every row block; register quad g holds
+    // columns 8 g + 4 (l/32) .. + 3 of the wave's 32-column fragment
+    const int cq = 4 * (lane / 32);
+    if (!SWIGLU) {
+        // fp32 output: a wave's 256 x 64 block goes through its quarter of the (now
+        // idle) LDS in chunks of 4 row blocks, written as register quads and read back
+        // along rows, so that every store instruction covers 4 rows x 256 contiguous
+        // bytes.  16-byte chunk c of row R sits at position c ^ (R % 16): the quads of
+        // 8 neighbouring rows and the 8 neighbouring chunks of a row both spread over
+        // all banks.
+        wg_barrier_nofence();   // every wave has read its last activation fragments
+        typedef float f32x4 __attribute__((ext_vector_type(4)));
+        char* stage = lds + wave * kSlotBytes;
+        static_assert(kSlotBytes == 128 * 64 * 4, "one chunk fills the wave's LDS quarter");
 #pragma unroll
-    for (int i = 0; i < NRB; ++i) {
+        for (int i0 = 0; i0 < NRB; i0 += 4) {
+            const int nb = NRB - i0 < 4 ? NRB - i0 : 4;   // row blocks in this chunk
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int mr = i * 32 + acc_row(r, lane);
-            if (mr >= rows) continue;
-            if (SWIGLU) {
-                const float av = acc[i][0][r], bv = acc[i][1][r];
-                const size_t off = static_cast<size_t>(row0 + mr) * ldc + nt * 128 + wave * 32 + col;
-                static_cast<bf16_t*>(C)[off] = f32_to_bf16((av / (1.f + __expf(-av))) * bv);
-            } else {
-                const size_t off = static_cast<size_t>(row0 + mr) * ldc + nt * 256 + wave * 64 + col;
-                static_cast<float*>(C)[off] = acc[i][0][r];
-                static_cast<float*>(C)[off + 32] = acc[i][1][r];
+            for (int ib = 0; ib < 4 && i0 + ib < NRB; ++ib) {
+                const int R = ib * 32 + lane % 32;
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int c = 8 * j + 2 * g + lane / 32;
+                        *reinterpret_cast<f32x4*>(stage + R * 256 + ((c ^ (R & 15)) * 16)) =
+                            f32x4{acc[i0 + ib][j][4 * g], acc[i0 + ib][j][4 * g + 1],
+                                  acc[i0 + ib][j][4 * g + 2], acc[i0 + ib][j][4 * g + 3]};
+                    }
+            }
+#pragma unroll
+            for (int q = 0; q < 8 * nb; ++q) {
+                const int R = 4 * q + lane / 16, mr = i0 * 32 + R;
+                const f32x4 v = *reinterpret_cast<const f32x4*>(stage + R * 256 + (lane % 16) * 16);
+                const int c = (lane % 16) ^ (R & 15);
+                if (mr < rows)
+                    *reinterpret_cast<f32x4*>(static_cast<float*>(C) +
+                                              static_cast<size_t>(row0 + mr) * ldc + nt * 256 +
+                                              wave * 64 + 4 * c) = v;
             }
         }
     }
+#pragma unroll
+    for (int i = 0; SWIGLU && i < NRB; ++i) {
+        const int mr = i * 32 + lane % 32;
+        if (mr >= rows) continue;
+        {
+            bf16_t* out = static_cast<bf16_t*>(C) + static_cast<size_t>(row0 + mr) * ldc +
+                          nt * 128 + wave * 32 + cq;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                float h[4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const float av = acc[i][0][4 * g + c], bv = acc[i][1][4 * g + c];
+                    h[c] = av * bv * __builtin_amdgcn_rcpf(1.f + __expf(-av));
+                }
+                // round-to-nearest-even in the conversion unit (v_cvt_pk_bf16_f32)
+                typedef float f32x4 __attribute__((ext_vector_type(4)));
+                typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+                const bf16x4 w = __builtin_convertvector(f32x4{h[0], h[1], h[2], h[3]}, bf16x4);
+                *reinterpret_cast<uint2*>(out + 8 * g) = __builtin_bit_cast(uint2, w);
+            }
+        }
+    }
+    ALLOCMOE_T256_PHASE(3);
 }
 
 #ifdef ALLOCMOE_TRACE
@@ -350,6 +415,11 @@ __global__ __launch_bounds__(kWaves* kWave, 1) void ffn_bf16_t256_kernel(StreamG
 }  // namespace
 
 #ifdef ALLOCMOE_TRACE
+extern "C" int allocmoe_debug_t256_phase(long long* host_out, int n_rows) {
+    return static_cast<int>(hipMemcpyFromSymbol(host_out, HIP_SYMBOL(t256_phase),
+                                                sizeof(long long) * 4 * n_rows, 0,
+                                                hipMemcpyDeviceToHost));
+}
 extern "C" int allocmoe_debug_t256_trace(long long* host_out, int n_rows) {
     return static_cast<int>(hipMemcpyFromSymbol(host_out, HIP_SYMBOL(t256_trace),
                                                 sizeof(long long) * 4 * n_rows, 0,
