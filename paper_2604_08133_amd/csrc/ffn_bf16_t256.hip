@@ -151,16 +151,23 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
 #pragma unroll
         for (int i = 0; i < NRB; ++i) a[i] = *reinterpret_cast<const bf16x8*>(base + i * (32 * 128));
     };
-    // The weight fragment is the first MFMA operand and the activation fragment
-    // the second, i.e. the unit forms the transposed 32x32 block: register r of lane
-    // l then holds the output of token row l%32 at column 8*(r/4) + 4*(l/32) + r%4,
-    // four consecutive columns per register quad, which the epilogue stores as one
-    // 8- or 16-byte word.
+    // SwiGLU half: the weight fragment is the first MFMA operand and the activation
+    // fragment the second, i.e. the unit forms the transposed 32x32 block: register r
+    // of lane l then holds the output of token row l%32 at column
+    // 8*(r/4) + 4*(l/32) + r%4, four consecutive columns per register quad, which
+    // the epilogue stores as one 8-byte word of bf16.  The fp32 half keeps the plain
+    // order (register r of lane l: row 8*(r/4) + 4*(l/32) + r%4, column l%32): its
+    // stores are 128 contiguous bytes per row either way, and measured faster so.
     auto multiply = [&](const bf16x8 (&a)[NRB], const bf16x8 (&b)[2]) {
 #pragma unroll
         for (int i = 0; i < NRB; ++i) {
-            acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[0], a[i], acc[i][0], 0, 0, 0);
-            acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[1], a[i], acc[i][1], 0, 0, 0);
+            if (SWIGLU) {
+                acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[0], a[i], acc[i][0], 0, 0, 0);
+                acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[1], a[i], acc[i][1], 0, 0, 0);
+            } else {
+                acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[0], acc[i][0], 0, 0, 0);
+                acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[1], acc[i][1], 0, 0, 0);
+            }
         }
     };
 
@@ -221,48 +228,24 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
     wait_vmcnt_le<0>();   // the surplus loads have landed before registers and LDS are reused
     ALLOCMOE_T256_PHASE(2);
 
-    // epilogue: lane l owns token row l%32 of every row block; register quad g holds
-    // columns 8 g + 4 (l/32) .. + 3 of the wave's 32-column fragment
-    const int cq = 4 * (lane / 32);
     if (!SWIGLU) {
-        // fp32 output: a wave's 256 x 64 block goes through its quarter of the (now
-        // idle) LDS in chunks of 4 row blocks, written as register quads and read back
-        // along rows, so that every store instruction covers 4 rows x 256 contiguous
-        // bytes.  16-byte chunk c of row R sits at position c ^ (R % 16): the quads of
-        // 8 neighbouring rows and the 8 neighbouring chunks of a row both spread over
-        // all banks.
-        wg_barrier_nofence();   // every wave has read its last activation fragments
-        typedef float f32x4 __attribute__((ext_vector_type(4)));
-        char* stage = lds + wave * kSlotBytes;
-        static_assert(kSlotBytes == 128 * 64 * 4, "one chunk fills the wave's LDS quarter");
+        // fp32 half: register r of lane l -> row 8*(r/4) + 4*(l/32) + r%4, column l%32
+        float* out = static_cast<float*>(C) + nt * 256 + wave * 64 + lane % 32;
 #pragma unroll
-        for (int i0 = 0; i0 < NRB; i0 += 4) {
-            const int nb = NRB - i0 < 4 ? NRB - i0 : 4;   // row blocks in this chunk
+        for (int i = 0; i < NRB; ++i) {
 #pragma unroll
-            for (int ib = 0; ib < 4 && i0 + ib < NRB; ++ib) {
-                const int R = ib * 32 + lane % 32;
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-#pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const int c = 8 * j + 2 * g + lane / 32;
-                        *reinterpret_cast<f32x4*>(stage + R * 256 + ((c ^ (R & 15)) * 16)) =
-                            f32x4{acc[i0 + ib][j][4 * g], acc[i0 + ib][j][4 * g + 1],
-                                  acc[i0 + ib][j][4 * g + 2], acc[i0 + ib][j][4 * g + 3]};
-                    }
-            }
-#pragma unroll
-            for (int q = 0; q < 8 * nb; ++q) {
-                const int R = 4 * q + lane / 16, mr = i0 * 32 + R;
-                const f32x4 v = *reinterpret_cast<const f32x4*>(stage + R * 256 + (lane % 16) * 16);
-                const int c = (lane % 16) ^ (R & 15);
-                if (mr < rows)
-                    *reinterpret_cast<f32x4*>(static_cast<float*>(C) +
-                                              static_cast<size_t>(row0 + mr) * ldc + nt * 256 +
-                                              wave * 64 + 4 * c) = v;
+            for (int r = 0; r < 16; ++r) {
+                const int mr = i * 32 + 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
+                if (mr >= rows) continue;
+                const size_t off = static_cast<size_t>(row0 + mr) * ldc;
+                out[off] = acc[i][0][r];
+                out[off + 32] = acc[i][1][r];
             }
         }
     }
+    // SwiGLU half: lane l owns token row l%32 of every row block; register quad g
+    // holds columns 8 g + 4 (l/32) .. + 3 of the wave's 32-column fragment
+    const int cq = 4 * (lane / 32);
 #pragma unroll
     for (int i = 0; SWIGLU && i < NRB; ++i) {
         const int mr = i * 32 + lane % 32;
