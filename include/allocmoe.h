@@ -177,7 +177,7 @@ allocmoe_status allocmoe_dispatch(const allocmoe_layer_desc *desc, const int32_t
  * intermediates stay in the workspace at the offsets of
  * allocmoe_workspace_layout.  All work is ordered after what `stream` holds at
  * the call and before what is enqueued on it afterwards.  For prefill-shaped
- * calls with a shared expert the library runs that expert's first GEMM on a
+ * calls with a shared expert the library runs that expert's GEMMs on a
  * stream of its own (one extra stream and two events per device, created on
  * first use, default priority) beside the selection; both ends are tied to
  * `stream` with events, no host synchronisation. */

@@ -367,14 +367,16 @@ allocmoe_status forward_impl(const allocmoe_layer_desc* desc, const void* X,
     const bool shared_tiled = tiled_shapes && T >= 128;
     const int bm = routed_tiled ? kTileRowsLarge : kTileRowsSmall;
     const int64_t max_tiles = max_tiles_for(desc, bm);
-    // The shared expert depends on nothing but X: its two GEMMs run on a side stream
-    // beside routing, selection and the routed experts' GEMMs, and the streams meet
-    // again before the combine.  Where the shared expert's GEMM fills the machine
-    // (tile kernel), the side stream starts after the routing kernel and the
-    // single-workgroup plan kernel is enqueued first, so that it gets a compute
-    // unit at once.  The measurement variant (ev != null) keeps every stage on the
-    // caller's stream.
-    const bool overlap = ev == nullptr && bf16 && Is > 0 && B > 0;
+    // The shared expert depends on nothing but X.  Where a group uses the tile kernel
+    // (prefill shapes), the shared expert's two GEMMs run on a side stream beside
+    // selection and the routed experts' GEMMs, and the streams meet again before the
+    // combine: the side stream starts after the routing kernel and the
+    // single-workgroup plan kernel is enqueued first, so that it gets a compute unit
+    // at once.  Decode shapes (both groups on the weight-streaming kernel) keep one
+    // stream and one launch per half for both groups: there the two event waits of a
+    // fork and join cost more than the overlap gains.  The measurement variant
+    // (ev != null) keeps every stage on the caller's stream.
+    const bool overlap = ev == nullptr && bf16 && Is > 0 && B > 0 && (routed_tiled || shared_tiled);
     SideStream* side = nullptr;
     StreamGroup s1, s2;   // the shared expert's two GEMMs
     if (bf16 && Is) {

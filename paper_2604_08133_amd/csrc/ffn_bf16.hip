@@ -35,10 +35,12 @@ __global__ __launch_bounds__(kStreamWaves* kWave) void ffn_bf16_stream_kernel(St
     constexpr int NACC = SWIGLU ? 2 : 1;
     __shared__ float red[kStreamWaves][NACC][16][kWave];
 
-    // the grid is the routed group's workgroups followed by the shared expert's
-    const bool first = static_cast<int64_t>(blockIdx.x) < g0.n_wg;
-    const StreamGroup& g = first ? g0 : g1;
-    const int bid = first ? blockIdx.x : blockIdx.x - static_cast<unsigned>(g0.n_wg);
+    // The grid is the shared expert's workgroups followed by the routed group's: the
+    // shared expert has few workgroups with a long stream each, which should start
+    // at once and run beside the routed ones instead of forming the launch's tail.
+    const bool dense = static_cast<int64_t>(blockIdx.x) < g1.n_wg;
+    const StreamGroup& g = dense ? g1 : g0;
+    const int bid = dense ? blockIdx.x : blockIdx.x - static_cast<unsigned>(g1.n_wg);
     const bf16_t* __restrict__ A = static_cast<const bf16_t*>(g.A);
     const bf16_t* __restrict__ Bp = static_cast<const bf16_t*>(g.Bp);
     const int32_t* __restrict__ row_map = g.row_map;
