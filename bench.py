@@ -34,10 +34,12 @@ def parse_args():
     p.add_argument("--budget-ratio", type=float, default=0.5,
                    help="layer budget as a fraction of T*K (the metric is quoted at 0.5)")
     p.add_argument("--layers", type=int, default=26, help="layers of the stack workload")
-    p.add_argument("--budgets", default="dirichlet", choices=["dirichlet", "alloc-l"],
+    p.add_argument("--budgets", default="dirichlet",
+                   choices=["dirichlet", "alloc-l", "ascending", "descending"],
                    help="stack workload: per-layer budgets from the seeded Dirichlet(2) draw "
                         "(the configuration the metric names) or from Alloc-L's dynamic "
-                        "programme on a seeded synthetic sensitivity matrix (budget = T*K_l)")
+                        "programme on a seeded synthetic sensitivity matrix, or from the "
+                        "Ascending / Descending schedule (budget = T*K_l)")
     p.add_argument("--selector", default="score", choices=["score", "top-p", "relative"],
                    help="token-level selector: Alloc-T (the metric's) or one of the calibrated "
                         "baselines of Appendix A.1, at the same budget")
@@ -155,6 +157,11 @@ def main():
         if args.budgets == "alloc-l":
             S = synth.sensitivity_matrix(args.layers, w.K)
             K_l, _ = B.allocmoe_alloc_l(S, int(round(args.budget_ratio * args.layers * w.K)))
+            budgets = [w.T * k for k in K_l]
+        elif args.budgets in ("ascending", "descending"):
+            kind = B.SCHEDULE_ASCENDING if args.budgets == "ascending" else B.SCHEDULE_DESCENDING
+            K_l = B.allocmoe_layer_schedule(kind, args.layers, w.K,
+                                            int(round(args.budget_ratio * args.layers * w.K)))
             budgets = [w.T * k for k in K_l]
         else:
             budgets = synth.stack_budgets(args.layers, w.T, w.K, w.K_base, args.budget_ratio)

@@ -250,6 +250,25 @@ allocmoe_status allocmoe_routing_stats(const allocmoe_layer_desc *desc, const fl
 allocmoe_status allocmoe_alloc_l(const double *S, int32_t L, int32_t K_orig, int64_t B,
                                  int32_t *K_out, double *cost_out);
 
+/* The heuristic layer-level schedules Alloc-L is compared with (appendix
+ * "Implementation Details of Baselines", layer-level baseline).  Ascending: an integer
+ * vector by rounded (halves up) linear interpolation from K_min at the first layer to
+ * K_max at the last, made non-decreasing with steps of at most one by a forward and a
+ * backward pass, then moved to the exact total B by sweeps over the internal layers
+ * (shallow to deep, one unit per layer and sweep, only where the vector stays
+ * non-decreasing, inside [K_min, K_max] and with steps of at most one).  K_min = 1 and
+ * K_max = K_orig; a B above their reach raises K_min, a B below it lowers K_max, until
+ * B fits.  Descending: the same vector in reverse layer order.  Writes K_out[L] (host)
+ * with sum K_i == B exactly, 1 <= K_i <= K_orig.  A single layer gets K = B.  Host-only.
+ * Errors: B < L or B > L * K_orig -> ALLOCMOE_EBUDGET; L < 1, K_orig < 1, unknown kind,
+ * K_out NULL -> ALLOCMOE_EINVAL. */
+typedef enum allocmoe_schedule {
+    ALLOCMOE_SCHEDULE_ASCENDING = 0,
+    ALLOCMOE_SCHEDULE_DESCENDING = 1
+} allocmoe_schedule;
+allocmoe_status allocmoe_layer_schedule(allocmoe_schedule kind, int32_t L, int32_t K_orig,
+                                        int64_t B, int32_t *K_out);
+
 const char *allocmoe_status_string(allocmoe_status status);
 
 #ifdef __cplusplus

@@ -22,7 +22,8 @@ EXPORTS = [
     "allocmoe_workspace_bytes", "allocmoe_workspace_layout", "allocmoe_packed_bytes",
     "allocmoe_pack_weights", "allocmoe_route", "allocmoe_route_from_scores",
     "allocmoe_dispatch", "allocmoe_moe_forward", "allocmoe_moe_forward_timed",
-    "allocmoe_alloc_l", "allocmoe_routing_stats", "allocmoe_status_string",
+    "allocmoe_alloc_l", "allocmoe_layer_schedule", "allocmoe_routing_stats",
+    "allocmoe_status_string",
 ]
 STAGES = ["route", "plan", "ffn1", "ffn2", "combine"]
 
@@ -224,6 +225,18 @@ def allocmoe_alloc_l(S, B: int):
                                    ctypes.c_int64(int(B)), out, ctypes.byref(cost)),
            "allocmoe_alloc_l")
     return list(out), cost.value
+
+
+SCHEDULE_ASCENDING, SCHEDULE_DESCENDING = 0, 1
+
+
+def allocmoe_layer_schedule(kind: int, L: int, K_orig: int, B: int):
+    """The Ascending (kind 0) or Descending (kind 1) per-layer allocation: L ints."""
+    out = (ctypes.c_int32 * L)()
+    _check(load().allocmoe_layer_schedule(ctypes.c_int(kind), ctypes.c_int32(L),
+                                          ctypes.c_int32(K_orig), ctypes.c_int64(int(B)), out),
+           "allocmoe_layer_schedule")
+    return list(out)
 
 
 # ------------------------------------------------ conveniences for tests/bench
