@@ -40,6 +40,9 @@ def parse_args():
                         "(the configuration the metric names) or from Alloc-L's dynamic "
                         "programme on a seeded synthetic sensitivity matrix, or from the "
                         "Ascending / Descending schedule (budget = T*K_l)")
+    p.add_argument("--weights", default="bf16", choices=["bf16", "fp8"],
+                   help="expert-weight format: bf16 (what the metric names) or the 8-bit variant "
+                        "(E4M3 codes + one fp32 scale per output column; streaming kernel only)")
     p.add_argument("--selector", default="score", choices=["score", "top-p", "relative"],
                    help="token-level selector: Alloc-T (the metric's) or one of the calibrated "
                         "baselines of Appendix A.1, at the same budget")
@@ -153,6 +156,8 @@ def main():
     # `--layers` independent layers (own weights, own input, own budget: layers of
     # a model interact only through the budgets Alloc-L gives them).
     layer_cpu = synth.make_layer(w, device="cpu") if on_cpu else None
+    fp8 = args.weights == "fp8"
+    wb = 1 if fp8 else 2          # bytes per stored expert-weight element
     if args.workload == "stack":
         if args.budgets == "alloc-l":
             S = synth.sensitivity_matrix(args.layers, w.K)
@@ -166,11 +171,12 @@ def main():
         else:
             budgets = synth.stack_budgets(args.layers, w.T, w.K, w.K_base, args.budget_ratio)
         works = [w.with_(budget=b) for b in budgets]
-        devs = [DeviceLayer(wl, synth.make_layer(wl, layer=i, device="cuda"))
+        devs = [DeviceLayer(wl, synth.make_layer(wl, layer=i, device="cuda"), weights_fp8=fp8)
                 for i, wl in enumerate(works)]
     else:
         works = [w]
-        devs = [DeviceLayer(w, layer_cpu if on_cpu else synth.make_layer(w, device="cuda"))]
+        devs = [DeviceLayer(w, layer_cpu if on_cpu else synth.make_layer(w, device="cuda"),
+                            weights_fp8=fp8)]
     selector = {"score": B.SELECT_SCORE, "top-p": B.SELECT_TOP_P, "relative": B.SELECT_RELATIVE}[args.selector]
     descs = [dv.desc(selector=selector) for dv in devs]
     ws = torch.empty(max(B.allocmoe_workspace_bytes(dc) for dc in descs), dtype=torch.uint8,
@@ -214,13 +220,15 @@ def main():
     d, I, Is, T = w.d, w.I, w.I_shared, w.T
     # ffn1 launch = routed rows + shared expert: W1,W3 once per active expert and
     # once for the shared expert; x rows in, H rows out
-    ffn1_bytes = (n_active_sum * 2 * d * I * 2 + pairs_sum * (d * 2 + I * 2)
-                  + nL * (2 * d * Is * 2 + T * (d * 2 + Is * 2) if Is else 0))
+    ffn1_bytes = (n_active_sum * 2 * d * I * wb + pairs_sum * (d * 2 + I * 2)
+                  + nL * (2 * d * Is * wb + T * (d * 2 + Is * 2) if Is else 0))
+    if fp8:   # the column scales
+        ffn1_bytes += n_active_sum * 2 * I * 4 + (nL * 2 * Is * 4 if Is else 0)
     ffn1_flops = pairs_sum * 2 * d * (2 * I) + nL * T * 2 * d * (2 * Is)
     dom = "ffn1"
     dom_ms = stages[dom]
-    if args.workload == "decode":
-        kernel_name = "ffn_bf16_stream_kernel<true>"
+    if args.workload == "decode" or fp8:
+        kernel_name = "ffn_bf16_stream_kernel<true, true>" if fp8 else "ffn_bf16_stream_kernel<true, false>"
         roof = {"bound": "hbm", "achieved": ffn1_bytes / (dom_ms * 1e-3) / 1e9,
                 "peak": HBM_PEAK_GBS, "unit": "GB/s"}
     else:
@@ -230,7 +238,7 @@ def main():
         # what the roofline allows at this arithmetic intensity: min(peak, flop/byte x HBM)
         roof["attainable"] = min(MFMA_BF16_PEAK_TFLOPS, ffn1_flops / ffn1_bytes * HBM_PEAK_GBS / 1e3)
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = traffic_from_profiles(args.workload, dom)
+    roof["traffic"] = None if fp8 else traffic_from_profiles(args.workload, dom)
     roof["kernel"] = kernel_name
     roof["kernel_ms"] = dom_ms / nL
     roof["launches_per_step"] = nL
@@ -238,7 +246,7 @@ def main():
     roof["algorithmic_flops"] = ffn1_flops / nL
 
     # whole-step algorithmic traffic and work (context for the step time)
-    step_bytes = (n_active_sum * 3 * d * I * 2 + nL * 3 * d * Is * 2   # expert + shared weights
+    step_bytes = (n_active_sum * 3 * d * I * wb + nL * 3 * d * Is * wb   # expert + shared weights
                   + nL * (T * d * 2 * 2 + d * w.E * 2)                 # X (gate), Y, Wg
                   + pairs_sum * (d * 2 + 2 * I * 2 + 2 * d * 4)        # x gather, H w+r, O w+r
                   + (nL * T * (d * 2 + 2 * Is * 2 + 2 * d * 4) if Is else 0))
@@ -263,7 +271,9 @@ def main():
                    "E": w.E, "I": w.I, "K": w.K, "K_base": w.K_base,
                    "budget": [wl.budget for wl in works] if nL > 1 else w.budget,
                    "budget_ratio": args.budget_ratio, "I_shared": w.I_shared, "selector": args.selector,
-                   "weights": "re-tiled once by allocmoe_pack_weights, outside the timed region"},
+                   "weights": ("bf16" if not fp8 else "e4m3 codes + fp32 column scales (bf16 matrix "
+                               "cores after widening in registers)")
+                   + ", re-tiled once by allocmoe_pack_weights, outside the timed region"},
         "roofline": roof,
         "step": step_info,
     }

@@ -69,7 +69,7 @@ typedef struct {
     int32_t I_shared;     /* 0 = no shared expert; else its (fused) intermediate width  */
     int32_t shared_gate;  /* 0: y += Shared(x);  1: y += sigmoid(x . w_sg) * Shared(x)  */
     int32_t dtype;        /* allocmoe_dtype of X, Y and every weight matrix             */
-    int32_t flags;        /* allocmoe_selector; every other bit must be 0               */
+    int32_t flags;        /* allocmoe_selector | optional ALLOCMOE_WEIGHTS_FP8; rest 0  */
 } allocmoe_layer_desc;
 
 /* Token-level selector (desc->flags).  All of them keep every token's first K_base
@@ -91,6 +91,29 @@ typedef enum {
     ALLOCMOE_SELECT_TOP_P = 1,
     ALLOCMOE_SELECT_RELATIVE = 2
 } allocmoe_selector;
+
+/* Expert-weight format flag, OR-ed into desc->flags (dtype BF16 only; d, I and I_shared
+ * multiples of 128).  The paper treats weight quantisation as orthogonal to budget
+ * allocation (Section 6); this is the variant for the weight-bound regimes (decode,
+ * small budgets), where the layer's time is the bytes of the active experts' weights.
+ * allocmoe_pack_weights then stores every expert matrix W[k][n] (routed and shared; the
+ * gate stays bf16) as one byte per element plus one fp32 scale per output column n:
+ *     scale[n] = max_k |W[k][n]| / 448          (fp32; 1 if the column is all zero)
+ *     q[k][n]  = the E4M3 code (OCP 8-bit floating point: 1 sign, 4 exponent bits with
+ *                bias 7, 3 mantissa bits, subnormals, no infinities, largest finite
+ *                magnitude 448) nearest to W[k][n] / scale[n] (fp32 division), ties to
+ *                the even mantissa, larger magnitudes saturating to 448
+ * standing for decode(q[k][n]) * scale[n].  The expert networks widen the codes to bf16
+ * in registers (exact), multiply on the bf16 matrix cores with fp32 accumulation and
+ * multiply the sum by the column's scale.  Every shape then runs on the weight-streaming
+ * kernel.  Packed buffer (byte offsets, each region 256-byte aligned, in this order):
+ * codes of W1|W3 [E], of W2 [E], of Ws1|Ws3, of Ws2 (same element order as the bf16
+ * buffer, a fragment of 32 k x 32 columns being 64 lanes x 16 bytes: lane l holds
+ * k = 32 kb + 8 (l/32) + i in byte i and k = 32 kb + 16 + 8 (l/32) + i in byte 8 + i,
+ * i = 0..7, column 32 nb + l%32; per expert and column block the W1 fragments along k,
+ * then the W3 fragments), the re-tiled bf16 gate, then the scales fp32 [E][2][I]
+ * (W1, W3), [E][d] (W2), [2][I_shared], [d]. */
+#define ALLOCMOE_WEIGHTS_FP8 0x100
 
 /* Weights, all device pointers, read-only.  gate_bias (fp32 [E], added to the
  * logits before the softmax) and the shared-expert fields may be NULL.

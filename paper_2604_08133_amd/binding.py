@@ -101,11 +101,14 @@ def _stream(stream) -> ctypes.c_void_p:
 SELECT_SCORE, SELECT_TOP_P, SELECT_RELATIVE = 0, 1, 2
 
 
+WEIGHTS_FP8 = 0x100
+
+
 def make_desc(T, d, E, I, K, K_base, budget, dtype, I_shared=0, shared_gate=False,
-              selector=SELECT_SCORE) -> LayerDesc:
+              selector=SELECT_SCORE, weights_fp8=False) -> LayerDesc:
     code = {"f32": F32, "bf16": BF16, torch.float32: F32, torch.bfloat16: BF16}.get(dtype, dtype)
     return LayerDesc(T, d, E, I, K, K_base, budget, I_shared, 1 if shared_gate else 0, code,
-                     int(selector))
+                     int(selector) | (WEIGHTS_FP8 if weights_fp8 else 0))
 
 
 def make_weights(Wg=None, gate_bias=None, W1=None, W3=None, W2=None, Ws1=None, Ws3=None,

@@ -39,10 +39,15 @@ Scratch scratch_of(const allocmoe_layer_desc* d) {
     return s;
 }
 
+inline int selector_of(const allocmoe_layer_desc* d) { return d->flags & 0xFF; }
+inline bool fp8_of(const allocmoe_layer_desc* d) { return (d->flags & ALLOCMOE_WEIGHTS_FP8) != 0; }
+
 allocmoe_status check_desc(const allocmoe_layer_desc* d) {
     if (d == nullptr) return ALLOCMOE_EINVAL;
     if (d->dtype != ALLOCMOE_F32 && d->dtype != ALLOCMOE_BF16) return ALLOCMOE_EINVAL;
-    if (d->flags < ALLOCMOE_SELECT_SCORE || d->flags > ALLOCMOE_SELECT_RELATIVE) return ALLOCMOE_EINVAL;
+    if ((d->flags & ~(0xFF | ALLOCMOE_WEIGHTS_FP8)) != 0) return ALLOCMOE_EINVAL;
+    if (selector_of(d) > ALLOCMOE_SELECT_RELATIVE) return ALLOCMOE_EINVAL;
+    if (fp8_of(d) && d->dtype != ALLOCMOE_BF16) return ALLOCMOE_EINVAL;
     if (d->T < 1 || d->d < 1 || d->E < 1 || d->I < 1 || d->K < 1) return ALLOCMOE_EINVAL;
     if (d->K_base < 0 || d->K_base > d->K || d->K > d->E) return ALLOCMOE_EINVAL;
     if (d->I_shared < 0 || (d->shared_gate != 0 && d->shared_gate != 1)) return ALLOCMOE_EINVAL;
@@ -51,6 +56,7 @@ allocmoe_status check_desc(const allocmoe_layer_desc* d) {
     if (static_cast<int64_t>(d->T) * d->K >= (1ll << 31)) return ALLOCMOE_ESHAPE;
     if (d->dtype == ALLOCMOE_BF16 && (d->d % 64 || d->I % 64 || d->I_shared % 64))
         return ALLOCMOE_ESHAPE;
+    if (fp8_of(d) && (d->d % 128 || d->I % 128 || d->I_shared % 128)) return ALLOCMOE_ESHAPE;
     if (d->budget < static_cast<int64_t>(d->T) * d->K_base ||
         d->budget > static_cast<int64_t>(d->T) * d->K)
         return ALLOCMOE_EBUDGET;
@@ -69,7 +75,7 @@ allocmoe_status layout_of(const allocmoe_layer_desc* d, allocmoe_ws_layout* L) {
         return at;
     };
     L->scratch = take(scratch_of(d).bytes);
-    L->sel_keys = take(d->flags != ALLOCMOE_SELECT_SCORE ? T * K * 4 : 0);
+    L->sel_keys = take(selector_of(d) != ALLOCMOE_SELECT_SCORE ? T * K * 4 : 0);
     L->scores = take(T * E * 4);
     L->topk_ids = take(T * K * 4);
     L->topk_s = take(T * K * 4);
@@ -101,6 +107,42 @@ PackedLayout packed_of(const allocmoe_layer_desc* d) {
     p.gate = p.ps2 + Is * dd;
     p.total_elems = p.gate + gate_packed_elems(d->d);
     return p;
+}
+
+// 8-bit expert weights: byte offsets.  The code regions keep the order and the
+// element counts of the bf16 layout (one byte per element); then the bf16 gate
+// matrix, then the fp32 column scales [E][2][I], [E][d], [2][I_shared], [d].
+struct PackedFp8 {
+    size_t q13, q2, qs13, qs2, gate, sc13, sc2, scs13, scs2, total;
+};
+
+PackedFp8 packed_fp8_of(const allocmoe_layer_desc* d) {
+    PackedFp8 p;
+    const size_t E = d->E, dd = d->d, I = d->I, Is = d->I_shared;
+    size_t off = 0;
+    auto take = [&off](size_t bytes) {
+        const size_t at = off;
+        off = align_up(off + bytes);
+        return at;
+    };
+    p.q13 = take(E * 2 * dd * I);
+    p.q2 = take(E * I * dd);
+    p.qs13 = take(2 * dd * Is);
+    p.qs2 = take(Is * dd);
+    p.gate = take(gate_packed_elems(d->d) * 2);
+    p.sc13 = take(E * 2 * I * 4);
+    p.sc2 = take(E * dd * 4);
+    p.scs13 = take(2 * Is * 4);
+    p.scs2 = take(Is ? dd * 4 : 0);
+    p.total = off;
+    return p;
+}
+
+// the re-tiled gate matrix inside the packed buffer
+inline const uint16_t* packed_gate(const allocmoe_layer_desc* d, const void* packed) {
+    if (fp8_of(d))
+        return reinterpret_cast<const uint16_t*>(static_cast<const char*>(packed) + packed_fp8_of(d).gate);
+    return static_cast<const uint16_t*>(packed) + packed_of(d).gate;
 }
 
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
@@ -150,7 +192,7 @@ allocmoe_status allocmoe_packed_bytes(const allocmoe_layer_desc* desc, size_t* b
     const allocmoe_status st = check_desc(desc);
     if (st != ALLOCMOE_OK) return st;
     if (desc->dtype != ALLOCMOE_BF16) return ALLOCMOE_EINVAL;
-    *bytes = align_up(packed_of(desc).total_elems * 2);
+    *bytes = fp8_of(desc) ? packed_fp8_of(desc).total : align_up(packed_of(desc).total_elems * 2);
     return ALLOCMOE_OK;
 }
 
@@ -163,10 +205,35 @@ allocmoe_status allocmoe_pack_weights(const allocmoe_layer_desc* desc,
     if (!w->Wg || !w->W1 || !w->W3 || !w->W2) return ALLOCMOE_EINVAL;
     if (desc->I_shared && (!w->Ws1 || !w->Ws3 || !w->Ws2)) return ALLOCMOE_EINVAL;
     if (desc->shared_gate && !w->w_sg) return ALLOCMOE_EINVAL;
-    const PackedLayout p = packed_of(desc);
-    if (packed_bytes < p.total_elems * 2 || !aligned(packed, kAlign)) return ALLOCMOE_EWORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     const int E = desc->E, d = desc->d, I = desc->I, Is = desc->I_shared;
+    if (fp8_of(desc)) {
+        const PackedFp8 q = packed_fp8_of(desc);
+        if (packed_bytes < q.total || !aligned(packed, kAlign)) return ALLOCMOE_EWORKSPACE;
+        char* out = static_cast<char*>(packed);
+        const size_t dd = d, II = I, SS = Is;
+        float* sc13 = at<float>(out, q.sc13);
+        ALLOCMOE_TRY(launch_pack_b_fp8(w->W1, E, d, I, out + q.q13, 2 * dd * II, 2 * dd * 32, 0, sc13,
+                                       2 * II, stream));
+        ALLOCMOE_TRY(launch_pack_b_fp8(w->W3, E, d, I, out + q.q13, 2 * dd * II, 2 * dd * 32, dd * 32,
+                                       sc13 + II, 2 * II, stream));
+        ALLOCMOE_TRY(launch_pack_b_fp8(w->W2, E, I, d, out + q.q2, II * dd, II * 32, 0,
+                                       at<float>(out, q.sc2), dd, stream));
+        ALLOCMOE_TRY(launch_pack_gate(w->Wg, desc->shared_gate ? w->w_sg : nullptr, d, E,
+                                      out + q.gate, stream));
+        if (Is) {
+            float* scs13 = at<float>(out, q.scs13);
+            ALLOCMOE_TRY(launch_pack_b_fp8(w->Ws1, 1, d, Is, out + q.qs13, 2 * dd * SS, 2 * dd * 32, 0,
+                                           scs13, 2 * SS, stream));
+            ALLOCMOE_TRY(launch_pack_b_fp8(w->Ws3, 1, d, Is, out + q.qs13, 2 * dd * SS, 2 * dd * 32,
+                                           dd * 32, scs13 + SS, 2 * SS, stream));
+            ALLOCMOE_TRY(launch_pack_b_fp8(w->Ws2, 1, Is, d, out + q.qs2, SS * dd, SS * 32, 0,
+                                           at<float>(out, q.scs2), dd, stream));
+        }
+        return ALLOCMOE_OK;
+    }
+    const PackedLayout p = packed_of(desc);
+    if (packed_bytes < p.total_elems * 2 || !aligned(packed, kAlign)) return ALLOCMOE_EWORKSPACE;
     uint16_t* out = static_cast<uint16_t*>(packed);
     const size_t dd = d, II = I;
     ALLOCMOE_TRY(launch_pack_b(w->W1, E, d, I, out + p.p13, 2 * dd * II, 2 * dd * 32, 0, stream));
@@ -191,14 +258,14 @@ allocmoe_status allocmoe_route(const allocmoe_layer_desc* desc, const void* X,
     if (st != ALLOCMOE_OK) return st;
     if (!X || !w || !w->Wg || !topk_ids || !topk_s || !keep_count) return ALLOCMOE_EINVAL;
     // the selection runs out of LDS; only the selector keys need device scratch
-    const bool keyed = desc->flags != ALLOCMOE_SELECT_SCORE;
+    const bool keyed = selector_of(desc) != ALLOCMOE_SELECT_SCORE;
     const size_t key_bytes = static_cast<size_t>(desc->T) * desc->K * 4;
     if (keyed && (ws == nullptr || ws_bytes < key_bytes || !aligned(ws, kAlign)))
         return ALLOCMOE_EWORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     if (desc->dtype == ALLOCMOE_BF16 && w->packed != nullptr) {
         if (!aligned(w->packed, kAlign) || !aligned(X, 16)) return ALLOCMOE_EINVAL;
-        const uint16_t* gp = static_cast<const uint16_t*>(w->packed) + packed_of(desc).gate;
+        const uint16_t* gp = packed_gate(desc, w->packed);
         ALLOCMOE_TRY(launch_route_mfma(X, gp, w->gate_bias, false, desc->T, desc->d, desc->E,
                                        desc->K, scores, topk_ids, topk_s, nullptr, stream));
     } else {
@@ -207,7 +274,7 @@ allocmoe_status allocmoe_route(const allocmoe_layer_desc* desc, const void* X,
     }
     const float* keys = topk_s;
     if (keyed) {
-        ALLOCMOE_TRY(launch_selector_keys(topk_s, desc->T, desc->K, desc->flags,
+        ALLOCMOE_TRY(launch_selector_keys(topk_s, desc->T, desc->K, selector_of(desc),
                                           static_cast<float*>(ws), stream));
         keys = static_cast<const float*>(ws);
     }
@@ -223,7 +290,7 @@ allocmoe_status allocmoe_route_from_scores(const allocmoe_layer_desc* desc, cons
     const allocmoe_status st = check_desc(desc);
     if (st != ALLOCMOE_OK) return st;
     if (!scores || !topk_ids || !topk_s || !keep_count) return ALLOCMOE_EINVAL;
-    const bool keyed = desc->flags != ALLOCMOE_SELECT_SCORE;
+    const bool keyed = selector_of(desc) != ALLOCMOE_SELECT_SCORE;
     const size_t key_bytes = static_cast<size_t>(desc->T) * desc->K * 4;
     if (keyed && (ws == nullptr || ws_bytes < key_bytes || !aligned(ws, kAlign)))
         return ALLOCMOE_EWORKSPACE;
@@ -231,7 +298,7 @@ allocmoe_status allocmoe_route_from_scores(const allocmoe_layer_desc* desc, cons
     ALLOCMOE_TRY(launch_topk_from_scores(scores, desc->T, desc->E, desc->K, topk_ids, topk_s, stream));
     const float* keys = topk_s;
     if (keyed) {
-        ALLOCMOE_TRY(launch_selector_keys(topk_s, desc->T, desc->K, desc->flags,
+        ALLOCMOE_TRY(launch_selector_keys(topk_s, desc->T, desc->K, selector_of(desc),
                                           static_cast<float*>(ws), stream));
         keys = static_cast<const float*>(ws);
     }
@@ -362,7 +429,10 @@ allocmoe_status forward_impl(const allocmoe_layer_desc* desc, const void* X,
     // the register-blocked tile kernel (256-row tiles), otherwise the
     // weight-streaming kernel (32-row tiles); decided per group from the descriptor
     // alone.
-    const bool tiled_shapes = bf16 && d % 256 == 0 && I % 128 == 0 && Is % 128 == 0;
+    // 8-bit weights exist for the weight-streaming kernel only (they halve the bytes
+    // of the weight-bound regimes); with them every shape takes that kernel.
+    const bool fp8 = fp8_of(desc);
+    const bool tiled_shapes = bf16 && !fp8 && d % 256 == 0 && I % 128 == 0 && Is % 128 == 0;
     const bool routed_tiled = tiled_shapes && B >= 24 * static_cast<int64_t>(E);
     const bool shared_tiled = tiled_shapes && T >= 128;
     const int bm = routed_tiled ? kTileRowsLarge : kTileRowsSmall;
@@ -387,6 +457,12 @@ allocmoe_status forward_impl(const allocmoe_layer_desc* desc, const void* X,
         s1.N = Is; s1.M_dense = T; s1.C = Hs; s1.ldc = Is;
         s2.A = Hs; s2.lda = Is; s2.Bp = pk + p.ps2; s2.group_stride = SS * dd; s2.Kd = Is;
         s2.N = d; s2.M_dense = T; s2.C = Os; s2.ldc = d;
+        if (fp8) {
+            const PackedFp8 q = packed_fp8_of(desc);
+            const char* pq = static_cast<const char*>(w->packed);
+            s1.Bp = pq + q.qs13; s1.scale = reinterpret_cast<const float*>(pq + q.scs13);
+            s2.Bp = pq + q.qs2; s2.scale = reinterpret_cast<const float*>(pq + q.scs2);
+        }
     }
     const StreamGroup none;
     auto fork_shared_expert = [&]() -> allocmoe_status {
@@ -412,7 +488,7 @@ allocmoe_status forward_impl(const allocmoe_layer_desc* desc, const void* X,
     // steps 1-2: scores and sorted candidates
     ALLOCMOE_MARK(ALLOCMOE_STAGE_ROUTE);
     if (bf16) {
-        const uint16_t* gp = static_cast<const uint16_t*>(w->packed) + packed_of(desc).gate;
+        const uint16_t* gp = packed_gate(desc, w->packed);
         ALLOCMOE_TRY(launch_route_mfma(X, gp, w->gate_bias, desc->shared_gate != 0, T, d, E, K,
                                        scores, topk_ids, topk_s, sgate, stream));
     } else {
@@ -427,8 +503,8 @@ allocmoe_status forward_impl(const allocmoe_layer_desc* desc, const void* X,
     // steps 3-4: Alloc-T selection, dispatch, tile map
     ALLOCMOE_MARK(ALLOCMOE_STAGE_PLAN);
     const float* sel_keys = topk_s;   // Alloc-T selects on the scores themselves
-    if (desc->flags != ALLOCMOE_SELECT_SCORE) {
-        ALLOCMOE_TRY(launch_selector_keys(topk_s, T, K, desc->flags, at<float>(base, L.sel_keys),
+    if (selector_of(desc) != ALLOCMOE_SELECT_SCORE) {
+        ALLOCMOE_TRY(launch_selector_keys(topk_s, T, K, selector_of(desc), at<float>(base, L.sel_keys),
                                           stream));
         sel_keys = at<float>(base, L.sel_keys);
     }
@@ -455,6 +531,12 @@ allocmoe_status forward_impl(const allocmoe_layer_desc* desc, const void* X,
             r1.max_tiles = max_tiles; r1.C = H; r1.ldc = I;
             r2.A = H; r2.lda = I; r2.Bp = pk + p.p2; r2.group_stride = II * dd; r2.Kd = I;
             r2.N = d; r2.tile_info = tile_info; r2.max_tiles = max_tiles; r2.C = O; r2.ldc = d;
+            if (fp8) {
+                const PackedFp8 q = packed_fp8_of(desc);
+                const char* pq = static_cast<const char*>(w->packed);
+                r1.Bp = pq + q.q13; r1.scale = reinterpret_cast<const float*>(pq + q.sc13);
+                r2.Bp = pq + q.q2; r2.scale = reinterpret_cast<const float*>(pq + q.sc2);
+            }
         }
         for (int half = 0; half < 2; ++half) {
             const bool swiglu = half == 0;

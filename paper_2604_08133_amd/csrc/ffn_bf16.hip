@@ -29,7 +29,25 @@ constexpr int kStreamUnroll = 8;
 // holds C[8*(r/4) + 4*(l/32) + r%4][l%32].
 __device__ __forceinline__ int acc_row(int r, int l) { return 8 * (r / 4) + 4 * (l / 32) + (r % 4); }
 
-template <bool SWIGLU>
+// 8 E4M3 codes (two dwords) -> 8 bf16 values, exactly (every E4M3 value is a bf16 value);
+// byte i of the pair is element i
+__device__ __forceinline__ bf16x8 fp8x8_to_bf16x8(uint32_t lo, uint32_t hi) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    const bf16x2 p0 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, 1.0f, false);
+    const bf16x2 p1 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, 1.0f, true);
+    const bf16x2 p2 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.0f, false);
+    const bf16x2 p3 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.0f, true);
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 w = {__builtin_bit_cast(uint32_t, p0), __builtin_bit_cast(uint32_t, p1),
+                     __builtin_bit_cast(uint32_t, p2), __builtin_bit_cast(uint32_t, p3)};
+    return __builtin_bit_cast(bf16x8, w);
+}
+
+// FP8: the weights are E4M3 codes with one scale per output column (pack.hip): a lane's
+// 16-byte load then holds its fragments of TWO k16 steps, the codes are widened to bf16
+// in registers (exact) and the column scale multiplies the fp32 sum at the end.  The
+// waves take blocks of 32 k round-robin; Kd must be a multiple of 128.
+template <bool SWIGLU, bool FP8>
 __global__ __launch_bounds__(kStreamWaves* kWave) void ffn_bf16_stream_kernel(StreamGroup g0,
                                                                              StreamGroup g1) {
     constexpr int NACC = SWIGLU ? 2 : 1;
@@ -65,16 +83,20 @@ __global__ __launch_bounds__(kStreamWaves* kWave) void ffn_bf16_stream_kernel(St
         rows = min(32, M_dense - row0);
     }
     const int lane = lane_id(), wave = threadIdx.x / kWave;
-    const int KB = Kd / 16;                 // k16 steps in total
-    const int steps = KB / kStreamWaves;    // per wave (Kd is a multiple of 64)
+    constexpr int kStepK = FP8 ? 32 : 16;   // k per load
+    const int KB = Kd / kStepK;             // loads per stream in total
+    const int steps = KB / kStreamWaves;    // per wave (Kd is a multiple of 64; 128 with FP8)
     // The waves take the k16 steps round-robin (wave w: steps w, w+4, ...), so at
     // any time the workgroup reads one contiguous run of each weight stream.
 
     // packed B: for this expert and column block, KB fragments of 64 x bf16x8
     // (W1 stream, then for SWIGLU the W3 stream)
+    // (a stream of one column block holds Kd * 32 elements: 2 bytes each, or 1 with FP8)
     const bf16x8* b1 = reinterpret_cast<const bf16x8*>(
-                           Bp + static_cast<size_t>(e) * group_stride +
-                           static_cast<size_t>(nb) * (static_cast<size_t>(NACC) * Kd * 32)) +
+                           reinterpret_cast<const char*>(Bp) +
+                           (static_cast<size_t>(e) * group_stride +
+                            static_cast<size_t>(nb) * (static_cast<size_t>(NACC) * Kd * 32)) *
+                               (FP8 ? 1 : 2)) +
                        static_cast<size_t>(wave) * kWave + lane;
     const bf16x8* b3 = b1 + static_cast<size_t>(KB) * kWave;
     constexpr size_t kStepB = static_cast<size_t>(kStreamWaves) * kWave;   // fragments per round
@@ -87,26 +109,39 @@ __global__ __launch_bounds__(kStreamWaves* kWave) void ffn_bf16_stream_kernel(St
         const int r = row0 + m;
         src = row_map ? row_map[r] : r;
     }
-    const bf16x8* ap =
-        reinterpret_cast<const bf16x8*>(A + static_cast<size_t>(src) * lda) + wave * 2 + kg;
-    constexpr int kStepA = kStreamWaves * 2;
+    const bf16x8* ap = reinterpret_cast<const bf16x8*>(A + static_cast<size_t>(src) * lda) +
+                       wave * (kStepK / 8) + kg;
+    constexpr int kStepA = kStreamWaves * (kStepK / 8);
 
     f32x16 acc1 = {0}, acc3 = {0};
     const bf16x8 zero = {0};
     // a batch of N steps: all loads first (they are in flight together), then the MFMAs
     auto batch = [&](int s, auto n_const) {
         constexpr int N = decltype(n_const)::value;
-        bf16x8 av[N], w1[N], w3[N];
+        bf16x8 av[N], av2[N], w1[N], w3[N];
 #pragma unroll
         for (int u = 0; u < N; ++u) {
             w1[u] = __builtin_nontemporal_load(b1 + static_cast<size_t>(s + u) * kStepB);
             if (SWIGLU) w3[u] = __builtin_nontemporal_load(b3 + static_cast<size_t>(s + u) * kStepB);
             av[u] = a_ok ? ap[(s + u) * kStepA] : zero;
+            if (FP8) av2[u] = a_ok ? ap[(s + u) * kStepA + 2] : zero;
         }
 #pragma unroll
         for (int u = 0; u < N; ++u) {
-            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[u], w1[u], acc1, 0, 0, 0);
-            if (SWIGLU) acc3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[u], w3[u], acc3, 0, 0, 0);
+            if (FP8) {
+                typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+                const u32x4 q1 = __builtin_bit_cast(u32x4, w1[u]);
+                acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[u], fp8x8_to_bf16x8(q1[0], q1[1]), acc1, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av2[u], fp8x8_to_bf16x8(q1[2], q1[3]), acc1, 0, 0, 0);
+                if (SWIGLU) {
+                    const u32x4 q3 = __builtin_bit_cast(u32x4, w3[u]);
+                    acc3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[u], fp8x8_to_bf16x8(q3[0], q3[1]), acc3, 0, 0, 0);
+                    acc3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av2[u], fp8x8_to_bf16x8(q3[2], q3[3]), acc3, 0, 0, 0);
+                }
+            } else {
+                acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[u], w1[u], acc1, 0, 0, 0);
+                if (SWIGLU) acc3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[u], w3[u], acc3, 0, 0, 0);
+            }
         }
     };
     int s = 0;
@@ -141,6 +176,11 @@ __global__ __launch_bounds__(kStreamWaves* kWave) void ffn_bf16_stream_kernel(St
             if (SWIGLU) v3 += red[w][NACC - 1][r][l];
         }
         const int mr = acc_row(r, l), n = nb * 32 + (l % 32);
+        if (FP8) {   // the column scales
+            const float* sc = g.scale + static_cast<size_t>(e) * NACC * N;
+            v1 *= sc[n];
+            if (SWIGLU) v3 *= sc[N + n];
+        }
         if (mr < rows) {
             const size_t off = static_cast<size_t>(row0 + mr) * ldc + n;
             if (SWIGLU)
@@ -162,10 +202,19 @@ hipError_t launch_ffn_bf16_stream(bool swiglu, StreamGroup routed, StreamGroup s
     const int64_t total = routed.n_wg + shared.n_wg;
     if (total <= 0) return hipSuccess;
     const dim3 grid(static_cast<unsigned>(total)), block(kStreamWaves * kWave);
-    if (swiglu)
-        hipLaunchKernelGGL(ffn_bf16_stream_kernel<true>, grid, block, 0, stream, routed, shared);
+    const bool fp8 = (routed.A ? routed.scale : shared.scale) != nullptr;
+    if (routed.A && shared.A && (routed.scale != nullptr) != (shared.scale != nullptr))
+        return hipErrorInvalidValue;   // one weight format per launch
+    if (fp8 && ((routed.A && routed.Kd % 128) || (shared.A && shared.Kd % 128)))
+        return hipErrorInvalidValue;
+    if (swiglu && fp8)
+        hipLaunchKernelGGL((ffn_bf16_stream_kernel<true, true>), grid, block, 0, stream, routed, shared);
+    else if (swiglu)
+        hipLaunchKernelGGL((ffn_bf16_stream_kernel<true, false>), grid, block, 0, stream, routed, shared);
+    else if (fp8)
+        hipLaunchKernelGGL((ffn_bf16_stream_kernel<false, true>), grid, block, 0, stream, routed, shared);
     else
-        hipLaunchKernelGGL(ffn_bf16_stream_kernel<false>, grid, block, 0, stream, routed, shared);
+        hipLaunchKernelGGL((ffn_bf16_stream_kernel<false, false>), grid, block, 0, stream, routed, shared);
     return hipGetLastError();
 }
 

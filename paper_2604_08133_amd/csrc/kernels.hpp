@@ -80,6 +80,10 @@ struct StreamGroup {
     int ldc = 0;
     int64_t n_wg = 0;          // filled by the launcher
     int xr = 1;                // dense group: XCDs along the row tiles (filled by the launcher)
+    // 8-bit weights (streaming kernel only): Bp holds E4M3 codes, one byte per element
+    // (group_stride in bytes), and scale[g][stream][n] the fp32 scale of every output
+    // column (stream: W1, W3 for the SwiGLU half; one for the plain half)
+    const float* scale = nullptr;
 };
 // routed experts' tiles and the shared expert's tiles in one launch
 hipError_t launch_ffn_bf16_stream(bool swiglu, StreamGroup routed, StreamGroup shared,
@@ -94,6 +98,15 @@ hipError_t launch_ffn_bf16_t256(bool swiglu, StreamGroup routed, StreamGroup sha
                                 hipStream_t stream);
 
 // ---- pack.hip : row-major [G][Kd][N] bf16 -> MFMA fragment order
+// 8-bit variant: per output column a scale (max |w| / 448, 1 for a zero column) and E4M3
+// codes of w / scale (nearest, ties to even mantissa, saturating), in fragments of
+// 32 k x 32 n: lane l holds 16 bytes, k = 32 kb + 8 (l/32) + i in bytes i = 0..7 and
+// k = 32 kb + 16 + 8 (l/32) + i in bytes 8 + i, column 32 nb + l%32.  Destination of
+// fragment (g, nb, kb): out + g*group_stride + nb*nblock_stride + base_off + kb*1024
+// (bytes).  scale_out[g*scale_stride + n].
+hipError_t launch_pack_b_fp8(const void* W, int G, int Kd, int N, void* out, size_t group_stride,
+                             size_t nblock_stride, size_t base_off, float* scale_out,
+                             size_t scale_stride, hipStream_t stream);
 hipError_t launch_pack_b(const void* W, int G, int Kd, int N, void* out,
                          size_t group_stride_elems, size_t nblock_stride_elems,
                          size_t base_off_elems, hipStream_t stream);

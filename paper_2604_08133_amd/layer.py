@@ -15,8 +15,9 @@ from .synth import Workload
 
 class DeviceLayer:
     def __init__(self, w: Workload, tensors: dict, device: str = "cuda:0",
-                 keep_canonical: bool = False):
+                 keep_canonical: bool = False, weights_fp8: bool = False):
         self.w = w
+        self.weights_fp8 = weights_fp8   # expert weights packed as E4M3 codes + column scales
         self.device = torch.device(device)
         self.dtype = torch.float32 if w.dtype == "f32" else torch.bfloat16
         t = {k: (v.to(self.device) if v is not None else None) for k, v in tensors.items()}
@@ -47,7 +48,7 @@ class DeviceLayer:
         w = self.w
         return B.make_desc(w.T, w.d, w.E, w.I, w.K, w.K_base if K_base is None else K_base,
                            w.budget if budget is None else budget, w.dtype, w.I_shared,
-                           w.shared_gate, selector=selector)
+                           w.shared_gate, selector=selector, weights_fp8=self.weights_fp8)
 
     def workspace(self, desc: B.LayerDesc) -> torch.Tensor:
         need = B.allocmoe_workspace_bytes(desc)

@@ -19,10 +19,13 @@ def scaled_err(got, want):
     return float((got.double() - want.double()).abs().max() / want.double().abs().max().clamp_min(1e-30))
 
 
-def check_layer(w, layer, budget=None, K_base=None, tokens=None, dev=None, tag=""):
+def check_layer(w, layer, budget=None, K_base=None, tokens=None, dev=None, tag="", ref_layer=None):
+    """ref_layer: the tensors the oracle computes with where they differ from what the
+    device layer was built from (quantised weights: the values the codes stand for)."""
     budget = w.budget if budget is None else budget
     K_base = w.K_base if K_base is None else K_base
     dev = dev or DeviceLayer(w, layer)
+    layer = ref_layer or layer
     print(f"forward {w.name} T={w.T} B={budget} Kb={K_base} {tag}", flush=True)
     Y = dev.forward(budget=budget, K_base=K_base)
     torch.cuda.synchronize()
