@@ -203,7 +203,10 @@ allocmoe_status allocmoe_dispatch(const allocmoe_layer_desc *desc, const int32_t
  * calls with a shared expert the library runs that expert's GEMMs on a
  * stream of its own (one extra stream and two events per device, created on
  * first use, default priority) beside the selection; both ends are tied to
- * `stream` with events, no host synchronisation. */
+ * `stream` with events, no host synchronisation.  The call only enqueues kernels
+ * and those two events (no allocation, no memset, no host wait), so it may be
+ * captured into a HIP graph and replayed; make the first call on a device outside
+ * a capture (it creates the side stream). */
 allocmoe_status allocmoe_moe_forward(const allocmoe_layer_desc *desc, const void *X,
                                      const allocmoe_weights *w, void *Y, void *ws,
                                      size_t ws_bytes, allocmoe_stream stream);
