@@ -313,7 +313,10 @@ __global__ __launch_bounds__(kWaves* kWave, 1) void ffn_bf16_t256_kernel(StreamG
         int sub = idx - S;
         if (g0.tile_info != nullptr) {
             const int tiles = g0.tile_info[0];
-            const int pair = sub / (2 * nt0) * kXcds + xcd, in_pair = sub % (2 * nt0);
+            // (pairs dealt in serpentine order: even rounds left to right, odd rounds
+            // right to left, which evens out the XCDs' totals of the sorted tile costs)
+            const int round = sub / (2 * nt0), in_pair = sub % (2 * nt0);
+            const int pair = round * kXcds + ((round & 1) ? kXcds - 1 - xcd : xcd);
             tile = 2 * pair + in_pair % 2;
             nt = in_pair / 2;
             if (tile >= tiles) return;   // the grid is sized for the host's bound
