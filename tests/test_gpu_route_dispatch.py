@@ -53,7 +53,9 @@ def budgets_for(T, K, Kb):
 
 @pytest.mark.parametrize("T,E,K", [(64, 8, 2), (32, 64, 6), (1, 64, 6), (63, 17, 5), (333, 60, 4),
                                    (1000, 64, 6), (1025, 64, 8), (4096, 64, 6), (8192, 64, 6),
-                                   (8192, 64, 8), (9000, 64, 6)])   # the last two: the large-size code path
+                                   (8192, 64, 8), (9000, 64, 6),    # these two: the large-size code path
+                                   (50, 64, 16), (2100, 64, 16),    # the widest candidate rows allowed
+                                   (7, 1, 1), (100, 2, 2), (300, 3, 1)])   # degenerate expert counts
 @pytest.mark.parametrize("Kb", [0, 1, 2])
 def test_bit_exact_distinct_scores(T, E, K, Kb):
     if Kb > K:
