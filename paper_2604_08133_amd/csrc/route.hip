@@ -129,9 +129,11 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 
 constexpr int kRmTok = 16;
-constexpr int kRmWaves = 8;
 
-template <bool GATE>
+// kRmWaves waves per workgroup: 8, or 16 for calls with few tokens (few workgroups,
+// each a chain of dependent steps: with 16 waves a wave's share of the hidden
+// dimension is one batch of loads and it finishes one token instead of two)
+template <bool GATE, int kRmWaves>
 __global__ __launch_bounds__(kRmWaves* kWave) void route_mfma_kernel(
     const bf16_t* __restrict__ X, const bf16_t* __restrict__ Gp, const float* __restrict__ bias,
     int T, int d, int E, int K, float* __restrict__ scores, int32_t* __restrict__ topk_ids,
@@ -274,15 +276,22 @@ hipError_t launch_route_mfma(const void* X, const void* gate_packed, const float
                              bool with_gate, int T, int d, int E, int K, float* scores,
                              int32_t* topk_ids, float* topk_s, float* sgate,
                              hipStream_t stream) {
-    const dim3 grid((T + kRmTok - 1) / kRmTok), block(kRmWaves * kWave);
+    const dim3 grid((T + kRmTok - 1) / kRmTok);
     const bf16_t* Xb = static_cast<const bf16_t*>(X);
     const bf16_t* Gp = static_cast<const bf16_t*>(gate_packed);
-    if (with_gate)
-        hipLaunchKernelGGL(route_mfma_kernel<true>, grid, block, 0, stream, Xb, Gp, bias, T, d, E,
-                           K, scores, topk_ids, topk_s, sgate);
+    const bool few = T <= 128;
+#define ALLOCMOE_ROUTE_LAUNCH(GATE, WAVES)                                                      \
+    hipLaunchKernelGGL((route_mfma_kernel<GATE, WAVES>), grid, dim3(WAVES * kWave), 0, stream, Xb, \
+                       Gp, bias, T, d, E, K, scores, topk_ids, topk_s, sgate)
+    if (with_gate && few)
+        ALLOCMOE_ROUTE_LAUNCH(true, 16);
+    else if (with_gate)
+        ALLOCMOE_ROUTE_LAUNCH(true, 8);
+    else if (few)
+        ALLOCMOE_ROUTE_LAUNCH(false, 16);
     else
-        hipLaunchKernelGGL(route_mfma_kernel<false>, grid, block, 0, stream, Xb, Gp, bias, T, d, E,
-                           K, scores, topk_ids, topk_s, sgate);
+        ALLOCMOE_ROUTE_LAUNCH(false, 8);
+#undef ALLOCMOE_ROUTE_LAUNCH
     return hipGetLastError();
 }
 
