@@ -248,8 +248,8 @@ def main():
     # whole-step algorithmic traffic and work (context for the step time)
     step_bytes = (n_active_sum * 3 * d * I * wb + nL * 3 * d * Is * wb   # expert + shared weights
                   + nL * (T * d * 2 * 2 + d * w.E * 2)                 # X (gate), Y, Wg
-                  + pairs_sum * (d * 2 + 2 * I * 2 + 2 * d * 4)        # x gather, H w+r, O w+r
-                  + (nL * T * (d * 2 + 2 * Is * 2 + 2 * d * 4) if Is else 0))
+                  + pairs_sum * (d * 2 + 2 * I * 2 + 2 * d * 2)        # x gather, H w+r, O w+r
+                  + (nL * T * (d * 2 + 2 * Is * 2 + 2 * d * 2) if Is else 0))
     step_flops = pairs_sum * 6 * d * I + nL * (T * 6 * d * Is + T * 2 * d * w.E)
     step_info = {
         "algorithmic_bytes": step_bytes, "algorithmic_flops": step_flops,

@@ -135,8 +135,9 @@ typedef struct {
  * intermediates it leaves behind (for inspection and tests).  Types and shapes:
  * scores f32 [T,E]; topk_ids i32 [T,K]; topk_s f32 [T,K]; keep_count i32 [T];
  * shared_gate f32 [T]; expert_offsets i32 [E+1]; row_token, row_rank i32 [B];
- * inv_row i32 [T,K]; H dtype [B,I]; Hs dtype [T,I_shared]; O f32 [B,d];
- * Os f32 [T,d]. */
+ * inv_row i32 [T,K]; H dtype [B,I]; Hs dtype [T,I_shared]; O dtype [B,d];
+ * Os dtype [T,d] (the experts' outputs are kept in the layer's dtype; Eq. (2)'s
+ * weighted sum over them is formed in fp32). */
 typedef struct {
     size_t scores, topk_ids, topk_s, keep_count, shared_gate;
     size_t expert_offsets, row_token, row_rank, inv_row;

@@ -87,8 +87,8 @@ allocmoe_status layout_of(const allocmoe_layer_desc* d, allocmoe_ws_layout* L) {
     L->inv_row = take(T * K * 4);
     L->H = take(B * d->I * es);
     L->Hs = take(T * d->I_shared * es);
-    L->O = take(B * d->d * 4);
-    L->Os = take(d->I_shared ? T * d->d * 4 : 0);
+    L->O = take(B * d->d * es);   // the experts' outputs are kept in the layer's dtype
+    L->Os = take(d->I_shared ? T * d->d * es : 0);
     L->total = off;
     return ALLOCMOE_OK;
 }
@@ -422,8 +422,8 @@ allocmoe_status forward_impl(const allocmoe_layer_desc* desc, const void* X,
     int32_t* tile_info = at<int32_t>(scr, s.tile_info);
     void* H = base + L.H;
     void* Hs = base + L.Hs;
-    float* O = at<float>(base, L.O);
-    float* Os = Is ? at<float>(base, L.Os) : nullptr;
+    void* O = base + L.O;
+    void* Os = Is ? base + L.Os : nullptr;
 
     // Kernel choice for step 5 (bf16): experts that see tens of rows or more use
     // the register-blocked tile kernel (256-row tiles), otherwise the
@@ -572,11 +572,11 @@ allocmoe_status forward_impl(const allocmoe_layer_desc* desc, const void* X,
         if (B > 0)
             ALLOCMOE_TRY(launch_ffn_f32(false, static_cast<const float*>(H), I, nullptr,
                                         static_cast<const float*>(w->W2), nullptr, I, d, tile_info,
-                                        s.max_tiles, 0, O, d, stream));
+                                        s.max_tiles, 0, static_cast<float*>(O), d, stream));
         if (Is)
             ALLOCMOE_TRY(launch_ffn_f32(false, static_cast<const float*>(Hs), Is, nullptr,
                                         static_cast<const float*>(w->Ws2), nullptr, Is, d, nullptr,
-                                        0, T, Os, d, stream));
+                                        0, T, static_cast<float*>(Os), d, stream));
     }
     // step 6: Eq. (2)
     ALLOCMOE_MARK(ALLOCMOE_STAGE_COMBINE);

@@ -1,7 +1,7 @@
 // bf16 expert networks on the matrix cores (Section 3.1: one feed-forward
 // execution per selected pair), fp32 accumulation, from weights re-tiled once
 // into MFMA fragment order (pack.hip):
-//   H = silu(A W1) * (A W3)   (SWIGLU, bf16 out)    or    O = A W2   (fp32 out).
+//   H = silu(A W1) * (A W3)   (SWIGLU)    or    O = A W2,   both stored as bf16.
 //
 // Weight-streaming kernel.  For token counts where an expert sees only a few
 // rows the layer is bound by reading each active expert's weights once from
@@ -186,7 +186,7 @@ __global__ __launch_bounds__(kStreamWaves* kWave) void ffn_bf16_stream_kernel(St
             if (SWIGLU)
                 static_cast<bf16_t*>(Cv)[off] = f32_to_bf16(v1 * v3 * __builtin_amdgcn_rcpf(1.f + __expf(-v1)));
             else
-                static_cast<float*>(Cv)[off] = v1;
+                static_cast<bf16_t*>(Cv)[off] = f32_to_bf16(v1);
         }
     }
 }

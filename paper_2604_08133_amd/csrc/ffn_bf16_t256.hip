@@ -1,6 +1,6 @@
 // bf16 expert networks on the matrix cores for prefill-shaped layers (Section
 // 3.1: one feed-forward execution per selected pair), fp32 accumulation:
-//   H = silu(A W1) * (A W3)   (SWIGLU, bf16 out)    or    O = A W2   (fp32 out).
+//   H = silu(A W1) * (A W3)   (SWIGLU)    or    O = A W2,   both stored as bf16.
 //
 // Register-blocked 256 x 256 tile on 4 waves (one per SIMD, all 512 registers).
 //
@@ -151,23 +151,16 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
 #pragma unroll
         for (int i = 0; i < NRB; ++i) a[i] = *reinterpret_cast<const bf16x8*>(base + i * (32 * 128));
     };
-    // SwiGLU half: the weight fragment is the first MFMA operand and the activation
-    // fragment the second, i.e. the unit forms the transposed 32x32 block: register r
-    // of lane l then holds the output of token row l%32 at column
-    // 8*(r/4) + 4*(l/32) + r%4, four consecutive columns per register quad, which
-    // the epilogue stores as one 8-byte word of bf16.  The fp32 half keeps the plain
-    // order (register r of lane l: row 8*(r/4) + 4*(l/32) + r%4, column l%32): its
-    // stores are 128 contiguous bytes per row either way, and measured faster so.
+    // The weight fragment is the first MFMA operand and the activation fragment the
+    // second, i.e. the unit forms the transposed 32x32 block: register r of lane l then
+    // holds the output of token row l%32 at column 8*(r/4) + 4*(l/32) + r%4, four
+    // consecutive columns per register quad, which the epilogue stores as one 8-byte
+    // word of bf16.
     auto multiply = [&](const bf16x8 (&a)[NRB], const bf16x8 (&b)[2]) {
 #pragma unroll
         for (int i = 0; i < NRB; ++i) {
-            if (SWIGLU) {
-                acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[0], a[i], acc[i][0], 0, 0, 0);
-                acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[1], a[i], acc[i][1], 0, 0, 0);
-            } else {
-                acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[0], acc[i][0], 0, 0, 0);
-                acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[1], acc[i][1], 0, 0, 0);
-            }
+            acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[0], a[i], acc[i][0], 0, 0, 0);
+            acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[1], a[i], acc[i][1], 0, 0, 0);
         }
     };
 
@@ -228,31 +221,19 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
     wait_vmcnt_le<0>();   // the surplus loads have landed before registers and LDS are reused
     ALLOCMOE_T256_PHASE(2);
 
-    if (!SWIGLU) {
-        // fp32 half: register r of lane l -> row 8*(r/4) + 4*(l/32) + r%4, column l%32
-        float* out = static_cast<float*>(C) + nt * 256 + wave * 64 + lane % 32;
-#pragma unroll
-        for (int i = 0; i < NRB; ++i) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int mr = i * 32 + 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
-                if (mr >= rows) continue;
-                const size_t off = static_cast<size_t>(row0 + mr) * ldc;
-                out[off] = acc[i][0][r];
-                out[off + 32] = acc[i][1][r];
-            }
-        }
-    }
-    // SwiGLU half: lane l owns token row l%32 of every row block; register quad g
-    // holds columns 8 g + 4 (l/32) .. + 3 of the wave's 32-column fragment
+    // epilogue: lane l owns token row l%32 of every row block; register quad g of
+    // fragment j holds columns 32 j + 8 g + 4 (l/32) .. + 3 of the wave's columns.
+    // SwiGLU: the two fragments are the W1 and W3 halves of the same 32 columns.
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
     const int cq = 4 * (lane / 32);
 #pragma unroll
-    for (int i = 0; SWIGLU && i < NRB; ++i) {
+    for (int i = 0; i < NRB; ++i) {
         const int mr = i * 32 + lane % 32;
         if (mr >= rows) continue;
-        {
-            bf16_t* out = static_cast<bf16_t*>(C) + static_cast<size_t>(row0 + mr) * ldc +
-                          nt * 128 + wave * 32 + cq;
+        bf16_t* out = static_cast<bf16_t*>(C) + static_cast<size_t>(row0 + mr) * ldc +
+                      nt * (SWIGLU ? 128 : 256) + wave * (SWIGLU ? 32 : 64) + cq;
+        if (SWIGLU) {
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 float h[4];
@@ -262,11 +243,20 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
                     h[c] = av * bv * __builtin_amdgcn_rcpf(1.f + __expf(-av));
                 }
                 // round-to-nearest-even in the conversion unit (v_cvt_pk_bf16_f32)
-                typedef float f32x4 __attribute__((ext_vector_type(4)));
-                typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
                 const bf16x4 w = __builtin_convertvector(f32x4{h[0], h[1], h[2], h[3]}, bf16x4);
                 *reinterpret_cast<uint2*>(out + 8 * g) = __builtin_bit_cast(uint2, w);
             }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const bf16x4 w = __builtin_convertvector(
+                        f32x4{acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2],
+                              acc[i][j][4 * g + 3]},
+                        bf16x4);
+                    *reinterpret_cast<uint2*>(out + 32 * j + 8 * g) = __builtin_bit_cast(uint2, w);
+                }
         }
     }
     ALLOCMOE_T256_PHASE(3);

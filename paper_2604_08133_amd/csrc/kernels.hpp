@@ -119,7 +119,7 @@ hipError_t launch_routing_stats(const float* scores, const int32_t* topk_ids, co
                                 float* metrics, hipStream_t stream);
 
 // ---- combine.hip : y_t = sum_j s[t,j] O[inv_row[t,j]] + g_t Os[t]
-hipError_t launch_combine(int out_dtype, const float* O, const float* Os, const int32_t* inv_row,
+hipError_t launch_combine(int dtype, const void* O, const void* Os, const int32_t* inv_row,
                           const float* topk_s, const int32_t* keep_count, const float* sgate,
                           int T, int d, int K, void* Y, hipStream_t stream);
 

@@ -83,7 +83,7 @@ class DeviceLayer:
             row_rank=B.ws_view(ws, L.row_rank, (Bn,), i32),
             inv_row=B.ws_view(ws, L.inv_row, (w.T, w.K), i32),
             H=B.ws_view(ws, L.H, (Bn, w.I), self.dtype),
-            O=B.ws_view(ws, L.O, (Bn, w.d), f32),
+            O=B.ws_view(ws, L.O, (Bn, w.d), self.dtype),
         )
         if w.shared_gate:
             out["shared_gate"] = B.ws_view(ws, L.shared_gate, (w.T,), f32)
