@@ -197,7 +197,8 @@ allocmoe_status allocmoe_dispatch(const allocmoe_layer_desc *desc, const int32_t
                                   int32_t *row_token, int32_t *row_rank, int32_t *inv_row,
                                   void *ws, size_t ws_bytes, allocmoe_stream stream);
 
-/* Steps 1-6.  X device [T,d], Y device [T,d], both desc->dtype.  The
+/* Steps 1-6.  X device [T,d], Y device [T,d], both desc->dtype (with BF16: both
+ * 16-byte aligned, else ALLOCMOE_EINVAL).  The
  * intermediates stay in the workspace at the offsets of
  * allocmoe_workspace_layout.  All work is ordered after what `stream` holds at
  * the call and before what is enqueued on it afterwards.  For prefill-shaped

@@ -396,6 +396,8 @@ allocmoe_status forward_impl(const allocmoe_layer_desc* desc, const void* X,
     const int Is = desc->I_shared;
     if (bf16) {
         if (!w->packed || !aligned(w->packed, kAlign)) return ALLOCMOE_EINVAL;
+        // rows are read and written in 16-byte pieces
+        if (!aligned(X, 16) || !aligned(Y, 16)) return ALLOCMOE_EINVAL;
     } else {
         if (!w->W1 || !w->W3 || !w->W2) return ALLOCMOE_EINVAL;
         if (Is && (!w->Ws1 || !w->Ws3 || !w->Ws2)) return ALLOCMOE_EINVAL;

@@ -37,7 +37,29 @@ __global__ __launch_bounds__(256) void combine_kernel(
     const int32_t* rows = inv_row + static_cast<size_t>(t) * K;
     const float* wts = topk_s + static_cast<size_t>(t) * K;
     const float g = Os ? (sgate ? sgate[t] : 1.f) : 0.f;
-    if ((d & 3) == 0) {
+    if (sizeof(TE) == 2 && (d & 7) == 0) {
+        // bf16: 8 elements (16 bytes) per lane and row
+        for (int c = threadIdx.x * 8; c < d; c += blockDim.x * 8) {
+            float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            auto add = [&](const TE* row, float wgt) {
+                const uint4 v = *reinterpret_cast<const uint4*>(row + c);
+                const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    acc[2 * i] += wgt * __uint_as_float(w[i] << 16);
+                    acc[2 * i + 1] += wgt * __uint_as_float(w[i] & 0xFFFF0000u);
+                }
+            };
+            for (int j = 0; j < kt; ++j) add(O + static_cast<size_t>(rows[j]) * d, wts[j]);
+            if (Os) add(Os + static_cast<size_t>(t) * d, g);
+            uint32_t w[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                w[i] = static_cast<uint32_t>(f32_to_bf16(acc[2 * i])) |
+                       (static_cast<uint32_t>(f32_to_bf16(acc[2 * i + 1])) << 16);
+            *reinterpret_cast<uint4*>(Y + static_cast<size_t>(t) * d + c) = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+    } else if ((d & 3) == 0) {
         for (int c = threadIdx.x * 4; c < d; c += blockDim.x * 4) {
             float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
             for (int j = 0; j < kt; ++j) {
