@@ -174,3 +174,21 @@ def test_forward_is_bitwise_reproducible():
         assert torch.equal(a.view(torch.int16), b.view(torch.int16))
         for k, v in dev.intermediates().items():
             assert torch.equal(ia[k].view(torch.uint8), v.view(torch.uint8)), k
+
+
+# ------------------------------------------------------------- argument checks
+
+def test_bf16_forward_rejects_misaligned_rows():
+    from paper_2604_08133_amd import binding as B
+    w = synth.Workload("align_bf16", T=8, d=128, E=4, I=64, K=2, K_base=1, budget=12, dtype="bf16")
+    dev = DeviceLayer(w, synth.make_layer(w, seed=41))
+    desc = dev.desc()
+    ws = dev.workspace(desc)
+    flat = torch.empty(w.T * w.d + 8, dtype=torch.bfloat16, device=dev.device)
+    Y_ok = flat[:w.T * w.d].view(w.T, w.d)
+    Y_odd = flat[1:w.T * w.d + 1].view(w.T, w.d)          # 2 bytes off a 16-byte boundary
+    B.allocmoe_moe_forward(desc, dev.X, dev.weights, Y_ok, ws)
+    with pytest.raises(B.AllocMoEError) as e:
+        B.allocmoe_moe_forward(desc, dev.X, dev.weights, Y_odd, ws)
+    assert e.value.status == B.EINVAL
+    torch.cuda.synchronize()
