@@ -118,7 +118,7 @@ __global__ __launch_bounds__(kRouteWaves* kWave) void route_kernel(
 }
 
 // ---------------------------------------------------------------------------
-// bf16 fast path: the gate GEMM on the matrix cores.  A workgroup of 8 waves
+// bf16 fast path: the gate GEMM on the matrix cores.  A workgroup of 16 waves
 // owns 16 tokens; the waves split the hidden dimension into slices of 32-wide
 // steps, each wave running v_mfma_f32_16x16x32_bf16 on its slice with the A
 // operand read straight from X (64 contiguous bytes per token and step) and the
@@ -129,11 +129,12 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 
 constexpr int kRmTok = 16;
+// 16 waves per workgroup: a workgroup is a chain of dependent steps (loads, reduction,
+// softmax, Top-K) and at most a few workgroups run per compute unit, so a wave's share of
+// the hidden dimension should be one batch of loads and a wave should finish one token
+constexpr int kRmWaves = 16;
 
-// kRmWaves waves per workgroup: 8, or 16 for calls with few tokens (few workgroups,
-// each a chain of dependent steps: with 16 waves a wave's share of the hidden
-// dimension is one batch of loads and it finishes one token instead of two)
-template <bool GATE, int kRmWaves>
+template <bool GATE>
 __global__ __launch_bounds__(kRmWaves* kWave) void route_mfma_kernel(
     const bf16_t* __restrict__ X, const bf16_t* __restrict__ Gp, const float* __restrict__ bias,
     int T, int d, int E, int K, float* __restrict__ scores, int32_t* __restrict__ topk_ids,
@@ -279,19 +280,13 @@ hipError_t launch_route_mfma(const void* X, const void* gate_packed, const float
     const dim3 grid((T + kRmTok - 1) / kRmTok);
     const bf16_t* Xb = static_cast<const bf16_t*>(X);
     const bf16_t* Gp = static_cast<const bf16_t*>(gate_packed);
-    const bool few = T <= 128;
-#define ALLOCMOE_ROUTE_LAUNCH(GATE, WAVES)                                                      \
-    hipLaunchKernelGGL((route_mfma_kernel<GATE, WAVES>), grid, dim3(WAVES * kWave), 0, stream, Xb, \
-                       Gp, bias, T, d, E, K, scores, topk_ids, topk_s, sgate)
-    if (with_gate && few)
-        ALLOCMOE_ROUTE_LAUNCH(true, 16);
-    else if (with_gate)
-        ALLOCMOE_ROUTE_LAUNCH(true, 8);
-    else if (few)
-        ALLOCMOE_ROUTE_LAUNCH(false, 16);
+    const dim3 block(kRmWaves * kWave);
+    if (with_gate)
+        hipLaunchKernelGGL(route_mfma_kernel<true>, grid, block, 0, stream, Xb, Gp, bias, T, d, E,
+                           K, scores, topk_ids, topk_s, sgate);
     else
-        ALLOCMOE_ROUTE_LAUNCH(false, 8);
-#undef ALLOCMOE_ROUTE_LAUNCH
+        hipLaunchKernelGGL(route_mfma_kernel<false>, grid, block, 0, stream, Xb, Gp, bias, T, d, E,
+                           K, scores, topk_ids, topk_s, sgate);
     return hipGetLastError();
 }
 
