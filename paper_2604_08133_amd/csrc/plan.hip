@@ -385,6 +385,28 @@ __global__ __launch_bounds__(NT) void plan_fast_kernel(
     const int tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
     ALLOCMOE_PLAN_STAMP(0);
 
+    // Candidate ids of this wave's batches (lane = token), all loaded up front so that
+    // the loads are in flight together, and kept in registers for both uses in the
+    // dispatch.  The 4-wave kernel (few tokens, one wave per SIMD, registers to spare)
+    // issues them before the selection, whose result they do not depend on; the 16-wave
+    // kernel after it.  Wider candidate rows than kIdsK fall back to loading them where
+    // they are used.
+    constexpr int kIdsK = 8;
+    constexpr int kMaxBatches = (NT == 1024 ? kFastMaxT : 1024) / kWave / NW;
+    const bool ids_held = DISPATCH && K <= kIdsK;
+    int held[kMaxBatches][kIdsK];
+    auto load_held = [&]() {
+        if (!ids_held) return;
+#pragma unroll
+        for (int bi = 0; bi < kMaxBatches; ++bi) {
+            const int t = (wave + bi * NW) * kWave + lane;
+#pragma unroll
+            for (int j = 0; j < kIdsK; ++j)
+                held[bi][j] = (t < T && j < K) ? topk_ids[static_cast<size_t>(t) * K + j] : 0;
+        }
+    };
+    if (NT == 256) load_held();
+
     if (SELECT) {
         const int P = K - Kb;
         const int n_pool = T * P;
@@ -560,22 +582,7 @@ __global__ __launch_bounds__(NT) void plan_fast_kernel(
     ALLOCMOE_PLAN_STAMP(4);
 
     const int n_batch = (T + kWave - 1) / kWave;
-    // Candidate ids of this wave's batches (lane = token), all loaded up front so that
-    // the loads are in flight together, and kept in registers for both uses below.
-    // Wider candidate rows than kIdsK fall back to loading them where they are used.
-    constexpr int kIdsK = 8;
-    constexpr int kMaxBatches = (NT == 1024 ? kFastMaxT : 1024) / kWave / NW;
-    const bool ids_held = K <= kIdsK;
-    int held[kMaxBatches][kIdsK];
-    if (ids_held) {
-#pragma unroll
-        for (int bi = 0; bi < kMaxBatches; ++bi) {
-            const int t = (wave + bi * NW) * kWave + lane;
-#pragma unroll
-            for (int j = 0; j < kIdsK; ++j)
-                held[bi][j] = (t < T && j < K) ? topk_ids[static_cast<size_t>(t) * K + j] : 0;
-        }
-    }
+    if (NT != 256) load_held();
     // ---- A: ballot words by bit-matrix transpose (lane e ends up with expert e's word)
 #pragma unroll
     for (int bi = 0; bi < kMaxBatches; ++bi) {
@@ -632,6 +639,9 @@ __global__ __launch_bounds__(NT) void plan_fast_kernel(
         if (tid <= E) expert_offsets[tid] = sh.expert_off[tid];
     }
     ALLOCMOE_PLAN_STAMP(6);
+    // ---- tile map, by the last wave, beside the other waves' share of phase C (with few
+    // tokens the last wave has no batch of its own)
+    if (tile_info != nullptr && wave == NW - 1) write_tile_map(sh.expert_off, E, bm, tile_info);
     // ---- C: place every pair
 #pragma unroll
     for (int bi = 0; bi < kMaxBatches; ++bi) {
@@ -666,8 +676,6 @@ __global__ __launch_bounds__(NT) void plan_fast_kernel(
         }
     }
     ALLOCMOE_PLAN_STAMP(7);
-    // ---- tile map
-    if (tile_info != nullptr && tid < kWave) write_tile_map(sh.expert_off, E, bm, tile_info);
     ALLOCMOE_PLAN_STAMP(8);
 }
 
