@@ -4,9 +4,10 @@
 A step is one pass of the whole hot path (route -> Alloc-T selection ->
 dispatch -> SwiGLU expert networks over the selected pairs + shared expert ->
 combine) over one batch of seeded synthetic input that is already resident in
-HBM.  Prints ONE JSON line ("Measurement").
+HBM.  Prints ONE JSON line: the metric, the roofline of the dominant kernel and the
+CPU oracle timed beside it.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload decode|prefill|qwen|stack]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload decode|prefill|qwen|olmoe|stack]
 """
 from __future__ import annotations
 

@@ -9,7 +9,7 @@ each token's sorted candidates (ids, s) [T,K] and its kept count k_t.  "Original
 routing keeps all K candidates of a token, budgeted routing the first k_t.
 
 Definitions, written out with numpy in fp64 (the paper names the statistics and
-leaves the details open; the readings are listed in the design doc):
+leaves the details open; these are the readings taken):
   load[e]   number of kept pairs whose expert is e
   wload[e]  sum of their routing scores ("weighted load"); p = wload / sum(wload)
   normalised entropy  -sum p ln p / ln E            (0 ln 0 = 0)
