@@ -82,3 +82,14 @@ def test_null_and_workspace_errors_without_launch():
     assert lib.allocmoe_packed_bytes(ctypes.byref(desc), ctypes.byref(n)) == B.EINVAL
     assert B.allocmoe_packed_bytes(good(dtype="bf16", d=128, I=256)) == \
         256 * (((8 * 3 * 128 * 256 + 5 * 16 * 128) * 2 + 255) // 256)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # the build is for one GPU: bench.py --gpus N > 1 exits with a message, before any GPU work
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=300)
+    assert r.returncode != 0
+    assert "--gpus 1" in r.stderr
