@@ -162,6 +162,19 @@ def test_deepseek_stack_layer_full_size_sampled(deepseek_big):
     check_layer(w, layer, budget=31337, tokens=toks[:3], dev=dev, tag="(ragged)")
 
 
+def test_qwen_full_size_sampled():
+    # configs[3] at the size bench.py times: T = 2048, 60 experts, Top-4, gated shared
+    # expert of width 5632; the swept budgets 0.5x / 0.75x / 1.0x; outputs on a seeded
+    # sample of tokens, indices on all of them.  Weights made on the CPU once.
+    w = synth.qwen_moe()
+    layer = synth.make_layer(w)
+    dev = DeviceLayer(w, layer)
+    toks = sample_tokens(w.T, 8, 3)
+    check_layer(w, layer, tokens=toks, dev=dev)                                  # 0.5x
+    check_layer(w, layer, budget=6144, tokens=toks[:3], dev=dev, tag="(0.75x)")
+    check_layer(w, layer, budget=8192, tokens=toks[:3], dev=dev, tag="(1.0x)")
+
+
 def test_forward_is_bitwise_reproducible():
     w = synth.Workload("repro", T=500, d=256, E=32, I=128, K=4, K_base=1, budget=1100,
                        dtype="bf16", I_shared=128, I_shared_each=128)
