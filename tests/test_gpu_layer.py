@@ -163,7 +163,7 @@ def test_deepseek_stack_layer_full_size_sampled(deepseek_big):
 
 
 def test_qwen_full_size_sampled():
-    # configs[3] at the size bench.py times: T = 2048, 60 experts, Top-4, gated shared
+    # the Qwen1.5-MoE-A2.7B-shaped layer at the size bench.py times: T = 2048, 60 experts, Top-4, gated shared
     # expert of width 5632; the swept budgets 0.5x / 0.75x / 1.0x; outputs on a seeded
     # sample of tokens, indices on all of them.  Weights made on the CPU once.
     w = synth.qwen_moe()
