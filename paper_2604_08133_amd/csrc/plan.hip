@@ -583,30 +583,20 @@ __global__ __launch_bounds__(NT) void plan_fast_kernel(
 
     const int n_batch = (T + kWave - 1) / kWave;
     if (NT != 256) load_held();
-    // ---- A: ballot words (word [batch][e]: bit t set iff token t of the batch keeps
-    // expert e).  Usual case (ids in registers): a token sets its bit in the words of
-    // the few experts it keeps -- integer ORs in LDS, order-free; the wave has zeroed
-    // its batch's words just before, and the LDS instructions of one wave take effect
-    // in program order.  Wide candidate rows: the token's 64-bit expert mask, then a
-    // 64 x 64 bit-matrix transpose (lane e ends up with expert e's word).
+    // ---- A: ballot words by bit-matrix transpose (lane e ends up with expert e's word)
 #pragma unroll
     for (int bi = 0; bi < kMaxBatches; ++bi) {
         const int b = wave + bi * NW;
         if (b >= n_batch) break;
         const int t = b * kWave + lane;
-        if (ids_held) {
-            unsigned long long* wb = reinterpret_cast<unsigned long long*>(&sh.words[b * kWave]);
-            wb[lane] = 0;
-            if (t < T) {
-                const int kt = min(K, sh.cnt[t]);
+        uint64_t mine = 0;
+        if (t < T) {
+            const int kt = min(K, sh.cnt[t]);
+            if (ids_held) {
 #pragma unroll
                 for (int j = 0; j < kIdsK; ++j)
-                    if (j < kt) atomicOr(&wb[held[bi][j] & (kWave - 1)], 1ull << lane);
-            }
-        } else {
-            uint64_t mine = 0;
-            if (t < T) {
-                const int kt = min(K, sh.cnt[t]);
+                    if (j < kt) mine |= 1ull << (held[bi][j] & (kWave - 1));
+            } else {
                 int ids[kMaxK];   // all loads first, so that they are in flight together
 #pragma unroll
                 for (int j = 0; j < kMaxK; ++j)
@@ -615,8 +605,8 @@ __global__ __launch_bounds__(NT) void plan_fast_kernel(
                 for (int j = 0; j < kMaxK; ++j)
                     if (j < kt) mine |= 1ull << (ids[j] & (kWave - 1));
             }
-            sh.words[b * kWave + lane] = wave_transpose64(mine);
         }
+        sh.words[b * kWave + lane] = wave_transpose64(mine);
     }
     __syncthreads();
     ALLOCMOE_PLAN_STAMP(5);
