@@ -28,40 +28,81 @@ __device__ __forceinline__ void store_elem(bf16_t* p, size_t i, float v) { p[i] 
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
 
+// The value of lane (l ^ S), S a power of two.  Within a row of 16 lanes the exchange is
+// done by the vector unit's lane permutations (DPP) instead of a trip through the LDS
+// crossbar: l^1 and l^2 are permutations inside a quad; reversing a quad is l^3,
+// reversing 8 lanes l^7, reversing 16 lanes l^15, so l^4 = (l^7)^3 and l^8 = (l^15)^7.
+// All 64 lanes must be active.
+template <int S>
+__device__ __forceinline__ uint32_t lane_xor(uint32_t v) {
+    static_assert(S == 1 || S == 2 || S == 4 || S == 8 || S == 16 || S == 32, "power of two");
+    const int x = static_cast<int>(v);
+    constexpr int kQuad1 = 0xB1, kQuad2 = 0x4E, kQuadRev = 0x1B;    // quad_perm [1,0,3,2] [2,3,0,1] [3,2,1,0]
+    constexpr int kRowMirror = 0x140, kRowHalfMirror = 0x141;
+    if (S == 1) return __builtin_amdgcn_mov_dpp(x, kQuad1, 0xF, 0xF, false);
+    if (S == 2) return __builtin_amdgcn_mov_dpp(x, kQuad2, 0xF, 0xF, false);
+    if (S == 4)
+        return __builtin_amdgcn_mov_dpp(__builtin_amdgcn_mov_dpp(x, kRowHalfMirror, 0xF, 0xF, false),
+                                        kQuadRev, 0xF, 0xF, false);
+    if (S == 8)
+        return __builtin_amdgcn_mov_dpp(__builtin_amdgcn_mov_dpp(x, kRowMirror, 0xF, 0xF, false),
+                                        kRowHalfMirror, 0xF, 0xF, false);
+    return static_cast<uint32_t>(__shfl_xor(x, S, kWave));
+}
+template <int S>
+__device__ __forceinline__ float lane_xor(float v) {
+    return __uint_as_float(lane_xor<S>(__float_as_uint(v)));
+}
+template <int S>
+__device__ __forceinline__ uint64_t lane_xor(uint64_t v) {
+    return static_cast<uint64_t>(lane_xor<S>(static_cast<uint32_t>(v))) |
+           (static_cast<uint64_t>(lane_xor<S>(static_cast<uint32_t>(v >> 32))) << 32);
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s, kWave);
+    v += lane_xor<32>(v);
+    v += lane_xor<16>(v);
+    v += lane_xor<8>(v);
+    v += lane_xor<4>(v);
+    v += lane_xor<2>(v);
+    v += lane_xor<1>(v);
     return v;
 }
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int s = 32; s >= 1; s >>= 1) v = fmaxf(v, __shfl_xor(v, s, kWave));
+    v = fmaxf(v, lane_xor<32>(v));
+    v = fmaxf(v, lane_xor<16>(v));
+    v = fmaxf(v, lane_xor<8>(v));
+    v = fmaxf(v, lane_xor<4>(v));
+    v = fmaxf(v, lane_xor<2>(v));
+    v = fmaxf(v, lane_xor<1>(v));
     return v;
 }
+// butterfly reductions over the 64 lanes: one exchange per power of two, largest first
+#define ALLOCMOE_BUTTERFLY(v, OP)      \
+    do {                                \
+        v = OP(v, lane_xor<32>(v));     \
+        v = OP(v, lane_xor<16>(v));     \
+        v = OP(v, lane_xor<8>(v));      \
+        v = OP(v, lane_xor<4>(v));      \
+        v = OP(v, lane_xor<2>(v));      \
+        v = OP(v, lane_xor<1>(v));      \
+    } while (0)
 __device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
-#pragma unroll
-    for (int s = 32; s >= 1; s >>= 1) {
-        uint64_t o = __shfl_xor(v, s, kWave);
-        v = o > v ? o : v;
-    }
+    auto mx = [](uint64_t a, uint64_t b) { return b > a ? b : a; };
+    ALLOCMOE_BUTTERFLY(v, mx);
     return v;
 }
 __device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
-#pragma unroll
-    for (int s = 32; s >= 1; s >>= 1) {
-        uint32_t o = __shfl_xor(v, s, kWave);
-        v = o < v ? o : v;
-    }
+    auto mn = [](uint32_t a, uint32_t b) { return b < a ? b : a; };
+    ALLOCMOE_BUTTERFLY(v, mn);
     return v;
 }
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
-#pragma unroll
-    for (int s = 32; s >= 1; s >>= 1) {
-        uint32_t o = __shfl_xor(v, s, kWave);
-        v = o > v ? o : v;
-    }
+    auto mx = [](uint32_t a, uint32_t b) { return b > a ? b : a; };
+    ALLOCMOE_BUTTERFLY(v, mx);
     return v;
 }
+#undef ALLOCMOE_BUTTERFLY
 // inclusive prefix sum over the 64 lanes
 __device__ __forceinline__ int wave_scan_incl(int v) {
     const int l = lane_id();

@@ -345,20 +345,26 @@ constexpr int kStageFloats = kFastMaxT * 3;
 
 // Transpose of a 64 x 64 bit matrix held one row per lane: afterwards lane e
 // holds column e (bit t = former bit e of lane t).
+template <int S>
+__device__ __forceinline__ uint64_t transpose_round(uint64_t x, int lane) {
+    // bits whose index has bit S clear
+    constexpr uint64_t m = S == 32   ? 0x00000000FFFFFFFFull
+                           : S == 16 ? 0x0000FFFF0000FFFFull
+                           : S == 8  ? 0x00FF00FF00FF00FFull
+                           : S == 4  ? 0x0F0F0F0F0F0F0F0Full
+                           : S == 2  ? 0x3333333333333333ull
+                                     : 0x5555555555555555ull;
+    const uint64_t y = lane_xor<S>(x);
+    return (lane & S) ? ((x & ~m) | ((y & ~m) >> S)) : ((x & m) | ((y & m) << S));
+}
 __device__ __forceinline__ uint64_t wave_transpose64(uint64_t x) {
     const int lane = lane_id();
-#pragma unroll
-    for (int s = 32; s >= 1; s >>= 1) {
-        // bits whose index has bit `s` clear
-        const uint64_t m = s == 32   ? 0x00000000FFFFFFFFull
-                           : s == 16 ? 0x0000FFFF0000FFFFull
-                           : s == 8  ? 0x00FF00FF00FF00FFull
-                           : s == 4  ? 0x0F0F0F0F0F0F0F0Full
-                           : s == 2  ? 0x3333333333333333ull
-                                     : 0x5555555555555555ull;
-        const uint64_t y = __shfl_xor(x, s, kWave);
-        x = (lane & s) ? ((x & ~m) | ((y & ~m) >> s)) : ((x & m) | ((y & m) << s));
-    }
+    x = transpose_round<32>(x, lane);
+    x = transpose_round<16>(x, lane);
+    x = transpose_round<8>(x, lane);
+    x = transpose_round<4>(x, lane);
+    x = transpose_round<2>(x, lane);
+    x = transpose_round<1>(x, lane);
     return x;
 }
 
