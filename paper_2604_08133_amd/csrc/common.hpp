@@ -103,14 +103,17 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
     return v;
 }
 #undef ALLOCMOE_BUTTERFLY
-// inclusive prefix sum over the 64 lanes
+// inclusive prefix sum over the 64 lanes (all active): inside each row of 16 lanes by
+// DPP shifts that fill with zero, then the totals of the rows before (lane 15 of a row
+// broadcast to the next row, lane 31 to the upper half)
 __device__ __forceinline__ int wave_scan_incl(int v) {
-    const int l = lane_id();
-#pragma unroll
-    for (int s = 1; s < kWave; s <<= 1) {
-        int o = __shfl_up(v, s, kWave);
-        if (l >= s) v += o;
-    }
+    constexpr int kRowShr = 0x110, kBcast15 = 0x142, kBcast31 = 0x143;
+    v += __builtin_amdgcn_update_dpp(0, v, kRowShr + 1, 0xF, 0xF, true);
+    v += __builtin_amdgcn_update_dpp(0, v, kRowShr + 2, 0xF, 0xF, true);
+    v += __builtin_amdgcn_update_dpp(0, v, kRowShr + 4, 0xF, 0xF, true);
+    v += __builtin_amdgcn_update_dpp(0, v, kRowShr + 8, 0xF, 0xF, true);
+    v += __builtin_amdgcn_update_dpp(0, v, kBcast15, 0xA, 0xF, false);
+    v += __builtin_amdgcn_update_dpp(0, v, kBcast31, 0xC, 0xF, false);
     return v;
 }
 
