@@ -427,16 +427,21 @@ allocmoe_status forward_impl(const allocmoe_layer_desc* desc, const void* X,
     void* O = base + L.O;
     void* Os = Is ? base + L.Os : nullptr;
 
-    // Kernel choice for step 5 (bf16): experts that see tens of rows or more use
-    // the register-blocked tile kernel (256-row tiles), otherwise the
+    // Kernel choice for step 5 (bf16): experts that see about eight rows or more on
+    // average use the register-blocked tile kernel (256-row tiles), otherwise the
     // weight-streaming kernel (32-row tiles); decided per group from the descriptor
-    // alone.
+    // alone.  Measured on DeepSeek-V2-Lite shapes the two kernels cross between 6
+    // and 9 rows per expert for the routed group (B = 6E: 174 us a step streaming,
+    // 182 tiled; B = 9E: 200 against 193; B = 12E: 227 against 201), and at about
+    // 128 tokens for the shared expert.
+    constexpr int64_t kRoutedTiledRowsPerExpert = 8;
+    constexpr int kSharedTiledTokens = 128;
     // 8-bit weights exist for the weight-streaming kernel only (they halve the bytes
     // of the weight-bound regimes); with them every shape takes that kernel.
     const bool fp8 = fp8_of(desc);
     const bool tiled_shapes = bf16 && !fp8 && d % 256 == 0 && I % 128 == 0 && Is % 128 == 0;
-    const bool routed_tiled = tiled_shapes && B >= 24 * static_cast<int64_t>(E);
-    const bool shared_tiled = tiled_shapes && T >= 128;
+    const bool routed_tiled = tiled_shapes && B >= kRoutedTiledRowsPerExpert * static_cast<int64_t>(E);
+    const bool shared_tiled = tiled_shapes && T >= kSharedTiledTokens;
     const int bm = routed_tiled ? kTileRowsLarge : kTileRowsSmall;
     const int64_t max_tiles = max_tiles_for(desc, bm);
     // The shared expert depends on nothing but X.  Where a group uses the tile kernel

@@ -119,9 +119,9 @@ def test_olmoe_shape_no_shared_expert():
     w = synth.olmoe(budget=4 * 256, T=256)
     layer = synth.make_layer(w)
     tokens = sample_tokens(w.T, 24, seed=8)           # outputs checked on a sample, indices on all
-    dev = check_layer(w, layer, tokens=tokens)                        # streaming kernel
+    dev = check_layer(w, layer, tokens=tokens)                        # 16 rows per expert: tile kernel
     check_layer(w, layer, budget=8 * 256, tokens=tokens, dev=dev)     # original Top-8, tile kernel
-    check_layer(w, layer, budget=256, K_base=1, tokens=tokens, dev=dev)   # Top-1 only
+    check_layer(w, layer, budget=256, K_base=1, tokens=tokens, dev=dev)   # Top-1 only: streaming kernel
 
 
 @pytest.fixture(scope="module")
