@@ -105,8 +105,8 @@ typedef enum {
  *                the even mantissa, larger magnitudes saturating to 448
  * standing for decode(q[k][n]) * scale[n].  The expert networks widen the codes to bf16
  * in registers (exact), multiply on the bf16 matrix cores with fp32 accumulation and
- * multiply the sum by the column's scale.  Every shape then runs on the weight-streaming
- * kernel.  Packed buffer (byte offsets, each region 256-byte aligned, in this order):
+ * multiply the sum by the column's scale (both expert-network kernels read either
+ * format; the kernel choice does not depend on it).  Packed buffer (byte offsets, each region 256-byte aligned, in this order):
  * codes of W1|W3 [E], of W2 [E], of Ws1|Ws3, of Ws2 (same element order as the bf16
  * buffer, a fragment of 32 k x 32 columns being 64 lanes x 16 bytes: lane l holds
  * k = 32 kb + 8 (l/32) + i in byte i and k = 32 kb + 16 + 8 (l/32) + i in byte 8 + i,

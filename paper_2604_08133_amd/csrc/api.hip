@@ -436,10 +436,9 @@ allocmoe_status forward_impl(const allocmoe_layer_desc* desc, const void* X,
     // 128 tokens for the shared expert.
     constexpr int64_t kRoutedTiledRowsPerExpert = 8;
     constexpr int kSharedTiledTokens = 128;
-    // 8-bit weights exist for the weight-streaming kernel only (they halve the bytes
-    // of the weight-bound regimes); with them every shape takes that kernel.
+    // Both kernels read bf16 or 8-bit weights (one format per layer).
     const bool fp8 = fp8_of(desc);
-    const bool tiled_shapes = bf16 && !fp8 && d % 256 == 0 && I % 128 == 0 && Is % 128 == 0;
+    const bool tiled_shapes = bf16 && d % 256 == 0 && I % 128 == 0 && Is % 128 == 0;
     const bool routed_tiled = tiled_shapes && B >= kRoutedTiledRowsPerExpert * static_cast<int64_t>(E);
     const bool shared_tiled = tiled_shapes && T >= kSharedTiledTokens;
     const int bm = routed_tiled ? kTileRowsLarge : kTileRowsSmall;

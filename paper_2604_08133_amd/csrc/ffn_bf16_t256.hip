@@ -22,6 +22,10 @@
 //    slots ahead; one workgroup barrier per 64 k.
 //  * Per 16 k a wave issues 2*NRB MFMAs for NRB LDS reads + 2 global loads, so a
 //    tile with fewer than 256 rows costs in proportion to its 32-row blocks.
+//  * 8-bit weights (E4M3 codes with one fp32 scale per output column): the same
+//    schedule with 8-byte instead of 16-byte weight loads; the codes are widened
+//    to bf16 (exactly) right before the MFMAs that use them and the column scales
+//    multiply the fp32 sums in the epilogue.
 #include <algorithm>
 #include <type_traits>
 
@@ -34,6 +38,8 @@ namespace {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kRows = kTileRowsLarge;   // rows per tile
 constexpr int kStepK = 64;              // contraction elements per ring slot
@@ -86,10 +92,27 @@ __device__ long long t256_phase[2][1 << 14][4];
 #define ALLOCMOE_T256_PHASE(i)
 #endif
 
-template <bool SWIGLU, int NRB, bool STREAM_ONCE>
+// 8 E4M3 codes (byte i = element i) -> 8 bf16 values, exactly
+__device__ __forceinline__ bf16x8 widen_fp8x8(uint2 q) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const bf16x2 p0 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(q.x, 1.0f, false);
+    const bf16x2 p1 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(q.x, 1.0f, true);
+    const bf16x2 p2 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(q.y, 1.0f, false);
+    const bf16x2 p3 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(q.y, 1.0f, true);
+    const u32x4 w = {__builtin_bit_cast(uint32_t, p0), __builtin_bit_cast(uint32_t, p1),
+                     __builtin_bit_cast(uint32_t, p2), __builtin_bit_cast(uint32_t, p3)};
+    return __builtin_bit_cast(bf16x8, w);
+}
+
+// b0, b1: the wave's two weight streams (bf16 fragments, or with FP8 the codes: a lane's
+// 16 bytes per 32 k hold its fragment of the even k16 step, then of the odd one);
+// sc0, sc1: with FP8 the scales of the 32 columns of each stream.
+template <bool SWIGLU, int NRB, bool STREAM_ONCE, bool FP8>
 __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda,
-                                          const int32_t* row_map, const bf16x8* b0,
-                                          const bf16x8* b1, int KT, int wave, int lane, int row0,
+                                          const int32_t* row_map, const void* b0,
+                                          const void* b1, const float* sc0, const float* sc1,
+                                          int KT, int wave, int lane, int row0,
                                           int rows, int nt, void* C, int ldc) {
     ALLOCMOE_T256_PHASE(0);
     f32x16 acc[NRB][2];
@@ -118,7 +141,8 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
         for (int i = 0; i < NRB; ++i)
             load_rows_to_lds(arow[i] + s * (kStepK / 8), lds_wave + slot * kSlotBytes + i * 4096);
     };
-    bf16x8 breg[kBRing][2];
+    typedef std::conditional_t<FP8, uint2, bf16x8> BFrag;
+    BFrag breg[kBRing][2];
     // Weight fragments come through buffer loads: a scalar descriptor per stream
     // (base, size), the lane's offset in a VGPR and the k16 step's offset in an SGPR,
     // so a load costs no address arithmetic on the vector unit; a step past the end
@@ -126,18 +150,27 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
     // reads are marked non-temporal: they need not displace what the caches hold
     // for tiles that share theirs.
     typedef __attribute__((__vector_size__(4 * sizeof(int)))) int i32x4;
-    const int stream_bytes = KT * kStepK * 32 * 2;
+    const int stream_bytes = KT * kStepK * 32 * (FP8 ? 1 : 2);
     const __amdgpu_buffer_rsrc_t rs0 = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<bf16x8*>(b0), 0, stream_bytes, 0x00020000);
+        const_cast<void*>(b0), 0, stream_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t rs1 = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<bf16x8*>(b1), 0, stream_bytes, 0x00020000);
+        const_cast<void*>(b1), 0, stream_bytes, 0x00020000);
     const int lane_off = lane * 16;
     auto load_b = [&](int q, int r) {
         constexpr int kAux = STREAM_ONCE ? 2 : 0;   // nt
-        const i32x4 v0 = __builtin_amdgcn_raw_buffer_load_b128(rs0, lane_off, q * 1024, kAux);
-        const i32x4 v1 = __builtin_amdgcn_raw_buffer_load_b128(rs1, lane_off, q * 1024, kAux);
-        breg[r][0] = __builtin_bit_cast(bf16x8, v0);
-        breg[r][1] = __builtin_bit_cast(bf16x8, v1);
+        if constexpr (FP8) {
+            typedef __attribute__((__vector_size__(2 * sizeof(int)))) int i32x2;
+            const int soff = (q >> 1) * 1024 + (q & 1) * 8;
+            const i32x2 v0 = __builtin_amdgcn_raw_buffer_load_b64(rs0, lane_off, soff, kAux);
+            const i32x2 v1 = __builtin_amdgcn_raw_buffer_load_b64(rs1, lane_off, soff, kAux);
+            breg[r][0] = __builtin_bit_cast(uint2, v0);
+            breg[r][1] = __builtin_bit_cast(uint2, v1);
+        } else {
+            const i32x4 v0 = __builtin_amdgcn_raw_buffer_load_b128(rs0, lane_off, q * 1024, kAux);
+            const i32x4 v1 = __builtin_amdgcn_raw_buffer_load_b128(rs1, lane_off, q * 1024, kAux);
+            breg[r][0] = __builtin_bit_cast(bf16x8, v0);
+            breg[r][1] = __builtin_bit_cast(bf16x8, v1);
+        }
     };
     // A operand of row block i, k16 chunk kc of a slot: lane l reads row m = l%32 of
     // the block, 16-byte chunk c = 2 kc + l/32 of that row, stored at position
@@ -156,7 +189,15 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
     // holds the output of token row l%32 at column 8*(r/4) + 4*(l/32) + r%4, four
     // consecutive columns per register quad, which the epilogue stores as one 8-byte
     // word of bf16.
-    auto multiply = [&](const bf16x8 (&a)[NRB], const bf16x8 (&b)[2]) {
+    auto multiply = [&](const bf16x8 (&a)[NRB], const BFrag (&bq)[2]) {
+        bf16x8 b[2];
+        if constexpr (FP8) {
+            b[0] = widen_fp8x8(bq[0]);
+            b[1] = widen_fp8x8(bq[1]);
+        } else {
+            b[0] = bq[0];
+            b[1] = bq[1];
+        }
 #pragma unroll
         for (int i = 0; i < NRB; ++i) {
             acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[0], a[i], acc[i][0], 0, 0, 0);
@@ -224,9 +265,15 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
     // epilogue: lane l owns token row l%32 of every row block; register quad g of
     // fragment j holds columns 32 j + 8 g + 4 (l/32) .. + 3 of the wave's columns.
     // SwiGLU: the two fragments are the W1 and W3 halves of the same 32 columns.
-    typedef float f32x4 __attribute__((ext_vector_type(4)));
-    typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
     const int cq = 4 * (lane / 32);
+    f32x4 scale[2][4];   // FP8: of the lane's columns, [fragment][quad]
+    if constexpr (FP8) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            scale[0][g] = *reinterpret_cast<const f32x4*>(sc0 + 8 * g + cq);
+            scale[1][g] = *reinterpret_cast<const f32x4*>(sc1 + 8 * g + cq);
+        }
+    }
 #pragma unroll
     for (int i = 0; i < NRB; ++i) {
         const int mr = i * 32 + lane % 32;
@@ -239,7 +286,11 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
                 float h[4];
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
-                    const float av = acc[i][0][4 * g + c], bv = acc[i][1][4 * g + c];
+                    float av = acc[i][0][4 * g + c], bv = acc[i][1][4 * g + c];
+                    if constexpr (FP8) {
+                        av *= scale[0][g][c];
+                        bv *= scale[1][g][c];
+                    }
                     h[c] = av * bv * __builtin_amdgcn_rcpf(1.f + __expf(-av));
                 }
                 // round-to-nearest-even in the conversion unit (v_cvt_pk_bf16_f32)
@@ -251,10 +302,10 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
             for (int j = 0; j < 2; ++j)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    const bf16x4 w = __builtin_convertvector(
-                        f32x4{acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2],
-                              acc[i][j][4 * g + 3]},
-                        bf16x4);
+                    f32x4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2],
+                               acc[i][j][4 * g + 3]};
+                    if constexpr (FP8) v *= scale[j][g];
+                    const bf16x4 w = __builtin_convertvector(v, bf16x4);
                     *reinterpret_cast<uint2*>(out + 32 * j + 8 * g) = __builtin_bit_cast(uint2, w);
                 }
         }
@@ -266,7 +317,7 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
 __device__ long long t256_trace[2][1 << 14][4];
 #endif
 
-template <bool SWIGLU>
+template <bool SWIGLU, bool FP8>
 __global__ __launch_bounds__(kWaves* kWave, 1) void ffn_bf16_t256_kernel(StreamGroup g0,
                                                                         StreamGroup g1) {
     __shared__ __attribute__((aligned(1024))) char lds[kSlots * kSlotBytes];
@@ -322,7 +373,7 @@ __global__ __launch_bounds__(kWaves* kWave, 1) void ffn_bf16_t256_kernel(StreamG
     }
 
     const bf16_t* __restrict__ A = static_cast<const bf16_t*>(g.A);
-    const bf16_t* __restrict__ Bp = static_cast<const bf16_t*>(g.Bp);
+    const char* __restrict__ Bp = static_cast<const char*>(g.Bp);
     const int32_t* __restrict__ row_map = g.row_map;
     const int32_t* __restrict__ tile_info = g.tile_info;
     const int lda = g.lda, Kd = g.Kd, ldc = g.ldc, M_dense = g.M_dense;
@@ -348,23 +399,32 @@ __global__ __launch_bounds__(kWaves* kWave, 1) void ffn_bf16_t256_kernel(StreamG
 #endif
 
     // B: the two fragment streams of this wave's 64 weight columns; a stream is
-    // Kd/16 fragments of 64 lanes x 16 B, contiguous
+    // Kd/16 fragments of 64 lanes x 16 B (FP8: Kd/32), contiguous
+    constexpr size_t kElemBytes = FP8 ? 1 : 2;
     const size_t stream_elems = static_cast<size_t>(Kd) * 32;
     const size_t sidx = SWIGLU ? static_cast<size_t>(4 * nt + wave) * 2
                                : static_cast<size_t>(8 * nt + 2 * wave);
     // (wave-uniform pointers: the loads take a scalar base and the lane's offset)
-    const bf16x8* b0 = reinterpret_cast<const bf16x8*>(
-        Bp + static_cast<size_t>(e) * g.group_stride + sidx * stream_elems);
-    const bf16x8* b1 = b0 + stream_elems / 8;
+    const char* b0 = Bp + (static_cast<size_t>(e) * g.group_stride + sidx * stream_elems) * kElemBytes;
+    const char* b1 = b0 + stream_elems * kElemBytes;
+    // FP8: scale[expert][stream][N]; SwiGLU: W1 and W3 scales of the wave's 32 columns,
+    // plain: of its two neighbouring 32-column blocks
+    const float* sc0 = nullptr;
+    const float* sc1 = nullptr;
+    if (FP8) {
+        const float* sc = g.scale + static_cast<size_t>(e) * (SWIGLU ? 2 : 1) * g.N;
+        sc0 = sc + nt * kColsPerTile + wave * (SWIGLU ? 32 : 64);
+        sc1 = SWIGLU ? sc0 + g.N : sc0 + 32;
+    }
 
 #define ALLOCMOE_T256_CASE(n)                                                                       \
     case n:                                                                                         \
         if (only_tile)                                                                              \
-            t256_body<SWIGLU, n, true>(lds, A, lda, row_map, b0, b1, KT, wave, lane, row0, rows, nt, \
-                                       g.C, ldc);                                                   \
+            t256_body<SWIGLU, n, true, FP8>(lds, A, lda, row_map, b0, b1, sc0, sc1, KT, wave, lane, \
+                                            row0, rows, nt, g.C, ldc);                              \
         else                                                                                        \
-            t256_body<SWIGLU, n, false>(lds, A, lda, row_map, b0, b1, KT, wave, lane, row0, rows,   \
-                                        nt, g.C, ldc);                                              \
+            t256_body<SWIGLU, n, false, FP8>(lds, A, lda, row_map, b0, b1, sc0, sc1, KT, wave,      \
+                                             lane, row0, rows, nt, g.C, ldc);                       \
         break;
     switch (n_rb) {   // uniform over the workgroup
         ALLOCMOE_T256_CASE(1)
@@ -438,10 +498,17 @@ hipError_t launch_ffn_bf16_t256(bool swiglu, StreamGroup routed, StreamGroup sha
     }
     if (per_xcd <= 0) return hipSuccess;
     const dim3 grid(static_cast<unsigned>(per_xcd * kXcds)), block(kWaves * kWave);
-    if (swiglu)
-        hipLaunchKernelGGL(ffn_bf16_t256_kernel<true>, grid, block, 0, stream, routed, shared);
+    const bool fp8 = (routed.A ? routed.scale : shared.scale) != nullptr;
+    if (routed.A && shared.A && (routed.scale != nullptr) != (shared.scale != nullptr))
+        return hipErrorInvalidValue;   // one weight format per launch
+    if (swiglu && fp8)
+        hipLaunchKernelGGL((ffn_bf16_t256_kernel<true, true>), grid, block, 0, stream, routed, shared);
+    else if (swiglu)
+        hipLaunchKernelGGL((ffn_bf16_t256_kernel<true, false>), grid, block, 0, stream, routed, shared);
+    else if (fp8)
+        hipLaunchKernelGGL((ffn_bf16_t256_kernel<false, true>), grid, block, 0, stream, routed, shared);
     else
-        hipLaunchKernelGGL(ffn_bf16_t256_kernel<false>, grid, block, 0, stream, routed, shared);
+        hipLaunchKernelGGL((ffn_bf16_t256_kernel<false, false>), grid, block, 0, stream, routed, shared);
     return hipGetLastError();
 }
 

@@ -95,7 +95,11 @@ def test_packed_codes_and_scales_bit_exact():
 @pytest.mark.parametrize("T,E,K,budget,Kb,I,Ish,gate", [
     (40, 8, 3, 70, 1, 128, 128, False),       # ragged row tiles, several experts per tile size
     (7, 4, 2, 9, 1, 256, 0, False),           # no shared expert
-    (300, 16, 4, 700, 0, 128, 256, True),     # prefill-sized call: still the streaming kernel
+    (300, 16, 4, 700, 0, 128, 256, True),     # routed and shared expert on the tile kernel
+    (700, 4, 2, 1000, 1, 256, 256, False),    # several 256-row tiles per expert, partial tiles
+    (100, 4, 3, 200, 1, 128, 128, False),     # routed on the tile kernel, shared streaming
+    (200, 64, 2, 300, 1, 128, 256, False),    # routed streaming, shared on the tile kernel
+    (513, 6, 4, 2052, 0, 384, 0, False),      # full budget, no shared expert
 ])
 def test_layer_with_fp8_weights(T, E, K, budget, Kb, I, Ish, gate):
     w = synth.Workload("fp8_layer", T=T, d=256, E=E, I=I, K=K, K_base=Kb, budget=budget,
@@ -106,13 +110,24 @@ def test_layer_with_fp8_weights(T, E, K, budget, Kb, I, Ish, gate):
     check_layer(w, layer, dev=DeviceLayer(w, layer, weights_fp8=True), ref_layer=ref, tag="fp8")
 
 
-def test_decode_shape_with_fp8_weights():
+def test_deepseek_shapes_with_fp8_weights():
+    # the decode workload (weight-streaming kernel), then 1024 tokens of the same layer
+    # (tile kernel: 48 rows per expert on average, popularity-biased), outputs on a
+    # seeded sample of tokens
     w = synth.deepseek_decode()
     layer = synth.make_layer(w)
     ref, _ = quantised_reference(layer)
     tokens = sample_tokens(w.T, 6, seed=9)
     check_layer(w, layer, dev=DeviceLayer(w, layer, weights_fp8=True), ref_layer=ref,
                 tokens=tokens, tag="fp8")
+    w2 = synth.deepseek_prefill().with_(T=1024, budget=3 * 1024)
+    extra = synth.make_layer(w2, only=("X", "bias"))
+    layer2, ref2 = dict(layer), dict(ref)
+    for k in ("X", "bias"):
+        layer2[k] = extra[k]
+        ref2[k] = extra[k].float()
+    check_layer(w2, layer2, dev=DeviceLayer(w2, layer2, weights_fp8=True), ref_layer=ref2,
+                tokens=sample_tokens(w2.T, 6, seed=10), tag="fp8 tile kernel")
 
 
 def test_fp8_flag_is_checked():
