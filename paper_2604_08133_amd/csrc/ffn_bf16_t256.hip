@@ -22,10 +22,12 @@
 //    slots ahead; one workgroup barrier per 64 k.
 //  * Per 16 k a wave issues 2*NRB MFMAs for NRB LDS reads + 2 global loads, so a
 //    tile with fewer than 256 rows costs in proportion to its 32-row blocks.
-//  * 8-bit weights (E4M3 codes with one fp32 scale per output column): the same
-//    schedule with 8-byte instead of 16-byte weight loads; the codes are widened
-//    to bf16 (exactly) right before the MFMAs that use them and the column scales
-//    multiply the fp32 sums in the epilogue.
+//  * 8-bit weights (E4M3 codes with one fp32 scale per output column): a lane's
+//    16-byte load holds its fragments of two k16 steps, so the ring of 8 loads per
+//    stream reaches 16 steps ahead (as many bytes in flight as with bf16) and a
+//    loop pass covers 16 steps; the codes are widened to bf16 (exactly) right
+//    before the MFMAs that use them and the column scales multiply the fp32 sums
+//    in the epilogue.
 #include <algorithm>
 #include <type_traits>
 
@@ -141,36 +143,25 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
         for (int i = 0; i < NRB; ++i)
             load_rows_to_lds(arow[i] + s * (kStepK / 8), lds_wave + slot * kSlotBytes + i * 4096);
     };
-    typedef std::conditional_t<FP8, uint2, bf16x8> BFrag;
-    BFrag breg[kBRing][2];
+    typedef __attribute__((__vector_size__(4 * sizeof(int)))) int i32x4;
+    i32x4 breg[kBRing][2];
     // Weight fragments come through buffer loads: a scalar descriptor per stream
     // (base, size), the lane's offset in a VGPR and the k16 step's offset in an SGPR,
     // so a load costs no address arithmetic on the vector unit; a step past the end
     // of the stream reads zeros instead of faulting.  Weights that no other tile
     // reads are marked non-temporal: they need not displace what the caches hold
     // for tiles that share theirs.
-    typedef __attribute__((__vector_size__(4 * sizeof(int)))) int i32x4;
     const int stream_bytes = KT * kStepK * 32 * (FP8 ? 1 : 2);
     const __amdgpu_buffer_rsrc_t rs0 = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<void*>(b0), 0, stream_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t rs1 = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<void*>(b1), 0, stream_bytes, 0x00020000);
     const int lane_off = lane * 16;
+    // ring entry r <- 16-byte unit q of both streams (bf16: k16 step q; FP8: steps 2q, 2q+1)
     auto load_b = [&](int q, int r) {
         constexpr int kAux = STREAM_ONCE ? 2 : 0;   // nt
-        if constexpr (FP8) {
-            typedef __attribute__((__vector_size__(2 * sizeof(int)))) int i32x2;
-            const int soff = (q >> 1) * 1024 + (q & 1) * 8;
-            const i32x2 v0 = __builtin_amdgcn_raw_buffer_load_b64(rs0, lane_off, soff, kAux);
-            const i32x2 v1 = __builtin_amdgcn_raw_buffer_load_b64(rs1, lane_off, soff, kAux);
-            breg[r][0] = __builtin_bit_cast(uint2, v0);
-            breg[r][1] = __builtin_bit_cast(uint2, v1);
-        } else {
-            const i32x4 v0 = __builtin_amdgcn_raw_buffer_load_b128(rs0, lane_off, q * 1024, kAux);
-            const i32x4 v1 = __builtin_amdgcn_raw_buffer_load_b128(rs1, lane_off, q * 1024, kAux);
-            breg[r][0] = __builtin_bit_cast(bf16x8, v0);
-            breg[r][1] = __builtin_bit_cast(bf16x8, v1);
-        }
+        breg[r][0] = __builtin_amdgcn_raw_buffer_load_b128(rs0, lane_off, q * 1024, kAux);
+        breg[r][1] = __builtin_amdgcn_raw_buffer_load_b128(rs1, lane_off, q * 1024, kAux);
     };
     // A operand of row block i, k16 chunk kc of a slot: lane l reads row m = l%32 of
     // the block, 16-byte chunk c = 2 kc + l/32 of that row, stored at position
@@ -189,14 +180,18 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
     // holds the output of token row l%32 at column 8*(r/4) + 4*(l/32) + r%4, four
     // consecutive columns per register quad, which the epilogue stores as one 8-byte
     // word of bf16.
-    auto multiply = [&](const bf16x8 (&a)[NRB], const BFrag (&bq)[2]) {
+    // step u of a loop pass
+    auto multiply = [&](const bf16x8 (&a)[NRB], int u) {
         bf16x8 b[2];
-        if constexpr (FP8) {
-            b[0] = widen_fp8x8(bq[0]);
-            b[1] = widen_fp8x8(bq[1]);
-        } else {
-            b[0] = bq[0];
-            b[1] = bq[1];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            if constexpr (FP8) {
+                const i32x4 q = breg[u / 2][j];
+                b[j] = widen_fp8x8((u & 1) ? uint2{static_cast<uint32_t>(q[2]), static_cast<uint32_t>(q[3])}
+                                           : uint2{static_cast<uint32_t>(q[0]), static_cast<uint32_t>(q[1])});
+            } else {
+                b[j] = __builtin_bit_cast(bf16x8, breg[u][j]);
+            }
         }
 #pragma unroll
         for (int i = 0; i < NRB; ++i) {
@@ -214,13 +209,19 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
     // The prologue issues slot 0 and then exactly the sequence of one loop pass
     // (weights of steps 0-2, slot 1, steps 3-6, slot 2, step 7), so that count
     // holds from the first pass on.  Loads past the end of the contraction re-read
-    // the last step (in bounds, never multiplied), which keeps the count uniform.
-    constexpr int kWaitA = 16 + NRB;
+    // the last step (in bounds, never multiplied) or, for the weights, read zeros
+    // past the end of the buffer, which keeps the count uniform.
+    // FP8: 16 steps per pass (4 slots), 2 weight loads after every second step (the
+    // ring entry both steps used, refilled for 16 steps later); between the loads of
+    // slot s+1 and the wait for it: 2 + (2 + NRB + 2) + 2.  The prologue keeps that
+    // count by placing the surplus weight loads before slot 1.
+    constexpr int kPass = FP8 ? 16 : 8;
+    constexpr int kWaitA = FP8 ? 8 + NRB : 16 + NRB;
     issue_a(0, 0);
 #pragma unroll
     for (int r = 0; r < kBRing; ++r) {
         load_b(r, r);
-        if (r == 2) issue_a(min(1, KT - 1), 1);
+        if (r == (FP8 ? 4 : 2)) issue_a(min(1, KT - 1), 1);
         if (r == 6) issue_a(min(2, KT - 1), 2);
     }
     wait_vmcnt_le<2 * kBRing + 2 * NRB>();   // slot 0 has landed (this wave's part)
@@ -229,9 +230,11 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
     read_a(0, 0, af[0]);
     ALLOCMOE_T256_PHASE(1);
 
-    for (int s2 = 0; s2 < KT; s2 += 2) {
+    // steps [4 s2, 4 s2 + STEPS) of the contraction
+    auto pass = [&](int s2, auto steps_const) {
+        constexpr int STEPS = decltype(steps_const)::value;
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < STEPS; ++u) {
             const int s = s2 + u / 4, kc = u % 4;
             __builtin_amdgcn_sched_barrier(0);
             __builtin_amdgcn_sched_barrier(0);
@@ -240,7 +243,7 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
                 read_a(s & 3, kc + 1, af[(u + 1) & 1]);
             else
                 read_a((s + 1) & 3, 0, af[(u + 1) & 1]);
-            multiply(af[u & 1], breg[u]);
+            multiply(af[u & 1], u);
 #pragma unroll
             for (int i = 0; i < NRB; ++i) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
@@ -248,7 +251,10 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
             }
             __builtin_amdgcn_sched_group_barrier(0x008, NRB, 0);     // the remaining MFMAs
             __builtin_amdgcn_sched_barrier(0);
-            load_b(4 * s2 + u + kBRing, u);
+            if constexpr (!FP8)
+                load_b(4 * s2 + u + kBRing, u);
+            else if (u & 1)
+                load_b(2 * s2 + u / 2 + kBRing, u / 2);
             if (kc == 2) {
                 // this wave's part of the next slot has landed; after the barrier
                 // everybody's has, and everybody is done with the slot before this one
@@ -257,7 +263,11 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
                 issue_a(min(s + 3, KT - 1), (s + 3) & 3);
             }
         }
-    }
+    };
+    int s2 = 0;
+    for (; s2 + kPass / 4 <= KT; s2 += kPass / 4) pass(s2, std::integral_constant<int, kPass>{});
+    // (KT is even; with 16-step passes a half pass may remain)
+    if (kPass == 16 && s2 < KT) pass(s2, std::integral_constant<int, 8>{});
     __builtin_amdgcn_sched_barrier(0);
     wait_vmcnt_le<0>();   // the surplus loads have landed before registers and LDS are reused
     ALLOCMOE_T256_PHASE(2);
@@ -342,7 +352,7 @@ __global__ __launch_bounds__(kWaves* kWave, 1) void ffn_bf16_t256_kernel(StreamG
     int S = 0, s_rows = 1;     // dense group: items and row tiles of this XCD
     const int xr = g1.xr, xc = kXcds / xr, xri = xcd % xr, xci = xcd / xr;
     if (g1.A != nullptr) {
-        const int tiles = (g1.M_dense + kRows - 1) / kRows;
+        const int tiles = (g1.M_dense + g1.dense_rows - 1) / g1.dense_rows;
         s_rows = (tiles - xri + xr - 1) / xr;
         S = s_rows * ((nt1 - xci + xc - 1) / xc);
     }
@@ -362,7 +372,7 @@ __global__ __launch_bounds__(kWaves* kWave, 1) void ffn_bf16_t256_kernel(StreamG
             nt = in_pair / 2;
             if (tile >= tiles) return;   // the grid is sized for the host's bound
         } else {   // a dense group in the first slot: its row tiles striped over the XCDs
-            const int tiles = (g0.M_dense + kRows - 1) / kRows;
+            const int tiles = (g0.M_dense + g0.dense_rows - 1) / g0.dense_rows;
             tile = sub / nt0 * kXcds + xcd;
             nt = sub % nt0;
             if (tile >= tiles) return;
@@ -387,9 +397,9 @@ __global__ __launch_bounds__(kWaves* kWave, 1) void ffn_bf16_t256_kernel(StreamG
         only_tile = ent[3] == 1;
     } else {
         e = 0;
-        row0 = tile * kRows;
-        rows = min(kRows, M_dense - row0);
-        only_tile = M_dense <= kRows;
+        row0 = tile * g.dense_rows;
+        rows = min(g.dense_rows, M_dense - row0);
+        only_tile = M_dense <= g.dense_rows;
     }
     const int lane = lane_id(), wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int n_rb = (rows + 31) / 32;   // 32-row blocks that hold real rows
@@ -463,9 +473,27 @@ extern "C" int allocmoe_debug_t256_trace(long long* host_out, int n_rows) {
 }
 #endif
 
+// Rows per tile of a dense group (every row tile reads the same weights): full
+// 256-row tiles where those fill the chip; with fewer tokens the smallest multiple of
+// 32 rows that still gives at most one workgroup per two compute units, so that the
+// group is one round of short workgroups instead of a few long ones (a tile costs in
+// proportion to its 32-row blocks; the weights it re-reads come from L2).  Measured on
+// DeepSeek-V2-Lite shapes, targets of 64 to 192 workgroups differ by < 2 %, 256 and
+// more lose 1-5 % from 2048 tokens on; against fixed 256-row tiles the step is 4-6 %
+// shorter at 128-512 tokens with bf16 weights, 9-13 % with 8-bit weights.
+int dense_tile_rows(int M, int col_tiles) {
+    constexpr int kTargetWorkgroups = 128;
+    int h = 32;
+    while (h < kRows && static_cast<int64_t>((M + h - 1) / h) * col_tiles > kTargetWorkgroups) h += 32;
+    return h;
+}
+
 hipError_t launch_ffn_bf16_t256(bool swiglu, StreamGroup routed, StreamGroup shared,
                                 hipStream_t stream) {
     const int cols = swiglu ? 128 : 256;
+    if (routed.A != nullptr && routed.tile_info == nullptr)
+        routed.dense_rows = dense_tile_rows(routed.M_dense, routed.N / cols);
+    if (shared.A != nullptr) shared.dense_rows = dense_tile_rows(shared.M_dense, shared.N / cols);
     // items per XCD; for the routed group an upper bound (the real tile count is
     // known on the device only)
     int64_t per_xcd = 0;
@@ -474,13 +502,13 @@ hipError_t launch_ffn_bf16_t256(bool swiglu, StreamGroup routed, StreamGroup sha
         if (routed.tile_info != nullptr)
             tiles = 2 * (((routed.max_tiles + 1) / 2 + kXcds - 1) / kXcds);   // whole pairs
         else
-            tiles = ((routed.M_dense + kRows - 1) / kRows + kXcds - 1) / kXcds;
+            tiles = ((routed.M_dense + routed.dense_rows - 1) / routed.dense_rows + kXcds - 1) / kXcds;
         per_xcd += tiles * (routed.N / cols);
     }
     if (shared.A != nullptr) {
         // XCD grid over (row tiles, column tiles): xr x 8/xr, chosen to minimise the
         // bytes the 8 L2s fetch in total: (8/xr) x activations + xr x weights
-        const int64_t rt = (shared.M_dense + kRows - 1) / kRows, ct = shared.N / cols;
+        const int64_t rt = (shared.M_dense + shared.dense_rows - 1) / shared.dense_rows, ct = shared.N / cols;
         const double a_bytes = static_cast<double>(shared.M_dense) * shared.Kd;
         const double b_bytes = static_cast<double>(shared.N) * shared.Kd * (swiglu ? 2 : 1);
         int best = 1;

@@ -80,7 +80,8 @@ struct StreamGroup {
     int ldc = 0;
     int64_t n_wg = 0;          // filled by the launcher
     int xr = 1;                // dense group: XCDs along the row tiles (filled by the launcher)
-    // 8-bit weights (streaming kernel only): Bp holds E4M3 codes, one byte per element
+    int dense_rows = 256;      // dense group, tile kernel: rows per tile (filled by the launcher)
+    // 8-bit weights: Bp holds E4M3 codes, one byte per element
     // (group_stride in bytes), and scale[g][stream][n] the fp32 scale of every output
     // column (stream: W1, W3 for the SwiGLU half; one for the plain half)
     const float* scale = nullptr;

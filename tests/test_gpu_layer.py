@@ -150,6 +150,13 @@ def test_deepseek_prefill_full_size_sampled(deepseek_big):
     toks = sample_tokens(w.T, 12, 1)
     check_layer(w, layer, tokens=toks, dev=dev)
     check_layer(w, layer, budget=24576, tokens=toks[:4], dev=dev, tag="(1.0x)")
+    # 640 tokens of the same layer: both groups on the tile kernel with partly filled
+    # tiles, the shared expert in tiles of fewer than 256 rows
+    del dev
+    w6 = w.with_(T=640, budget=3 * 640)
+    layer6 = dict(layer)
+    layer6["X"] = layer["X"][:640].contiguous()
+    check_layer(w6, layer6, tokens=sample_tokens(640, 6, 4), tag="(T=640)")
 
 
 def test_deepseek_stack_layer_full_size_sampled(deepseek_big):
