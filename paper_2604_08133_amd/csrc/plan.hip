@@ -427,19 +427,34 @@ __global__ __launch_bounds__(NT) void plan_fast_kernel(
             // Small pool (decode-shaped calls): every pool entry counts the entries that
             // precede it in the order (score descending, token ascending, rank
             // ascending) and is kept iff fewer than B' do.
+            // The order as one unsigned number per entry: key, then the complement of the
+            // pool index (equal keys: the lower index is the larger number).  A wave keeps
+            // 64 entries of the pool at a time in a register pair and broadcasts them one
+            // by one through scalar registers, so the inner loop touches no memory.
+            static_assert(kDirectPool <= 256 && kDirectPool <= NT, "one entry per thread, 8-bit index");
             for (int t = tid; t < T; t += NT) sh.cnt[t] = Kb;
-            for (int i = tid; i < n_pool; i += NT)
-                sh.hist[i] = ordered_key(topk_s[static_cast<size_t>(i / P) * K + Kb + i % P]);
+            for (int i = tid; i < kDirectPool; i += NT)
+                sh.hist[i] = i < n_pool
+                                 ? ordered_key(topk_s[static_cast<size_t>(i / P) * K + Kb + i % P])
+                                 : 0u;   // below every real key (no finite score maps to 0)
             __syncthreads();
-            for (int i = tid; i < n_pool; i += NT) {
-                const uint32_t k = sh.hist[i];
+            if (wave * kWave < n_pool) {   // uniform per wave
+                const uint64_t mine = (static_cast<uint64_t>(sh.hist[tid]) << 8) | (255u - tid);
                 int before = 0;
-#pragma unroll 8
-                for (int o = 0; o < n_pool; ++o) {
-                    const uint32_t ko = sh.hist[o];
-                    before += (ko > k || (ko == k && o < i)) ? 1 : 0;
+                for (int c = 0; c * kWave < n_pool; ++c) {
+                    const int o = c * kWave + lane;
+                    const uint64_t theirs = (static_cast<uint64_t>(sh.hist[o]) << 8) | (255u - o);
+                    const int lo = static_cast<int>(static_cast<uint32_t>(theirs));
+                    const int hi = static_cast<int>(static_cast<uint32_t>(theirs >> 32));
+#pragma unroll
+                    for (int l = 0; l < kWave; ++l) {
+                        const uint64_t other =
+                            static_cast<uint32_t>(__builtin_amdgcn_readlane(lo, l)) |
+                            (static_cast<uint64_t>(static_cast<uint32_t>(__builtin_amdgcn_readlane(hi, l))) << 32);
+                        before += other > mine ? 1 : 0;
+                    }
                 }
-                if (before < want) atomicAdd(&sh.cnt[i / P], 1);   // integer adds: order-free
+                if (tid < n_pool && before < want) atomicAdd(&sh.cnt[tid / P], 1);   // integer adds: order-free
             }
         } else {
             for (int t = tid; t < T; t += NT) sh.cnt[t] = Kb;
