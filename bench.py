@@ -43,7 +43,7 @@ def parse_args():
                         "Ascending / Descending schedule (budget = T*K_l)")
     p.add_argument("--weights", default="bf16", choices=["bf16", "fp8"],
                    help="expert-weight format: bf16 (what the metric names) or the 8-bit variant "
-                        "(E4M3 codes + one fp32 scale per output column; streaming kernel only)")
+                        "(E4M3 codes + one fp32 scale per output column)")
     p.add_argument("--selector", default="score", choices=["score", "top-p", "relative"],
                    help="token-level selector: Alloc-T (the metric's) or one of the calibrated "
                         "baselines of Appendix A.1, at the same budget")
@@ -228,12 +228,13 @@ def main():
     ffn1_flops = pairs_sum * 2 * d * (2 * I) + nL * T * 2 * d * (2 * Is)
     dom = "ffn1"
     dom_ms = stages[dom]
-    if args.workload == "decode" or fp8:
-        kernel_name = "ffn_bf16_stream_kernel<true, true>" if fp8 else "ffn_bf16_stream_kernel<true, false>"
+    targs = "<true, true>" if fp8 else "<true, false>"   # <SwiGLU half, 8-bit weights>
+    if args.workload == "decode":
+        kernel_name = "ffn_bf16_stream_kernel" + targs
         roof = {"bound": "hbm", "achieved": ffn1_bytes / (dom_ms * 1e-3) / 1e9,
                 "peak": HBM_PEAK_GBS, "unit": "GB/s"}
     else:
-        kernel_name = "ffn_bf16_t256_kernel<true>"
+        kernel_name = "ffn_bf16_t256_kernel" + targs
         roof = {"bound": "mfma", "achieved": ffn1_flops / (dom_ms * 1e-3) / 1e12,
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s"}
         # what the roofline allows at this arithmetic intensity: min(peak, flop/byte x HBM)
