@@ -17,13 +17,14 @@
  * All matrices are row-major.  Expert e's matrices: W1[e] and W3[e] are
  * [d, I], W2[e] is [I, d]; the expert network is
  *     E_e(x) = ( silu(x W1_e) (*) (x W3_e) ) W2_e ,  silu(a) = a / (1 + exp(-a))
- * (the paper only says "one feed-forward execution"; the SwiGLU form, with W1
- * on the gated branch, is the workload definition of the evaluated models).
+ * (the paper speaks only of a feed-forward execution per activation; the SwiGLU
+ * form, with W1 on the gated branch, is the workload definition of the evaluated
+ * models).
  *
  * Parity pins: every function here is pinned by tests/test_oracle_*.py (brute
  * force of the selection problem, reduction to plain Top-K, budget
  * conservation, dense-vs-dispatched Eq. (2), closed forms and a library fp64
- * re-computation).  Nothing is "parity unpinned".
+ * re-computation).  No function here is left without a pin.
  */
 #include <math.h>
 #include <stdint.h>
@@ -52,7 +53,7 @@ static const void *offset_elems(const void *p, int dtype, size_t n)
 /* ---------------------------------------------------- Eq. (1): gate, softmax */
 
 /* logits[t,e] = sum_h X[t,h] * W_gate[h,e] (+ bias[e]);  Section 3.1, Eq. (1):
- * "projecting it with W_gate in R^{H x N}".  The additive per-expert bias is
+ * the hidden state times the gate matrix of shape [H, N].  The additive per-expert bias is
  * not in the paper; it is the synthetic workload's popularity skew and is
  * applied to the logits before the softmax.  bias may be NULL. */
 void oracle_gate_logits(const void *X, const void *Wg, const float *bias,
@@ -117,7 +118,7 @@ static int cmp_cand(const void *pa, const void *pb)
     return (a->id > b->id) - (a->id < b->id); /* equal scores: lower expert id first */
 }
 
-/* Per-token Top-K_orig candidates, "sorted in descending order" (Section 3.3,
+/* Per-token Top-K_orig candidates in descending order of score (Section 3.3,
  * Eq. (6) and the paragraph after Eq. (9)).  Whole row sorted by (score down,
  * expert id up); the first K entries are the candidates. */
 void oracle_topk(const float *scores, int T, int E, int K, int32_t *ids, float *s)
@@ -200,8 +201,8 @@ int oracle_alloc_t(const float *topk_s, int T, int K, int Kb, int64_t B,
 /* --------------------------------------------------- expert-sorted dispatch */
 
 /* Rows of the selected (token, expert) pairs in the order (expert up, token
- * up).  Not in the paper (it is how "one feed-forward execution" per activated
- * expert, Section 3.1, is batched); the order is unique because a token
+ * up).  Not in the paper (it is how the feed-forward executions of the activated
+ * experts, Section 3.1, are batched); the order is unique because a token
  * selects an expert at most once.
  *   expert_offsets[e] .. expert_offsets[e+1]  = rows of expert e
  *   row_token[r], row_rank[r]                  = the pair behind row r
