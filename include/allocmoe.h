@@ -11,8 +11,8 @@
  *                                  (Section 3.3, Eqs. (7)-(9) and the procedure after them)
  *   4. an expert-sorted dispatch of the selected (token, expert) pairs
  *   5. the SwiGLU expert networks over only the selected pairs, plus the
- *      always-on shared expert of the workload                 (Section 3.1, "one
- *      feed-forward execution" per activation)
+ *      always-on shared expert of the workload                 (Section 3.1: a
+ *      feed-forward execution per activation)
  *   6. y_t = sum_i w_{t,i} E_i(x_t), w = retained score or 0   (Section 3.1, Eq. (2))
  * The per-layer budget B is an input: it is what Alloc-L's offline dynamic
  * programme (Section 3.2, Eqs. (3)-(5)) hands to the layer, as T*K_l.

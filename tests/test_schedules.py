@@ -69,8 +69,8 @@ def test_oracle_closed_forms():
 
 
 def test_oracle_against_brute_force_on_small_inputs():
-    # all non-decreasing, step <= 1 sequences from lo to hi (ends fixed, as the text's
-    # "internal layers" implies) with the right sum; where exactly one exists for the
+    # all non-decreasing, step <= 1 sequences from lo to hi (ends fixed: the text adjusts
+    # only the layers between the first and the last) with the right sum; where exactly one exists for the
     # widest feasible (lo, hi) the oracle must return it, otherwise one of them
     for L in range(3, 8):
         for K in (2, 3, 4):
