@@ -99,6 +99,14 @@ def test_bf16_tiled_kernel_paths(T, E, K, budget, Kb, I, Ish, bias):
     check_layer(w, synth.make_layer(w, seed=51))
 
 
+def test_bf16_more_tokens_than_the_single_workgroup_plan_takes():
+    # T = 9000: selection and dispatch on the large-size kernels, tile map with many
+    # tiles per expert; indices on all tokens, outputs on a seeded sample
+    w = synth.Workload("big_T_bf16", T=9000, d=256, E=16, I=128, K=4, K_base=1, budget=20000,
+                       dtype="bf16", I_shared=128, I_shared_each=128, bias_kind="zipf")
+    check_layer(w, synth.make_layer(w, seed=52), tokens=sample_tokens(w.T, 16, 5))
+
+
 # ------------------------------------------------- the paper-shaped workloads
 
 def test_deepseek_decode_full():
