@@ -5,6 +5,7 @@
 
 #include "kernels.hpp"
 
+#include <algorithm>
 #include <mutex>
 
 namespace {
@@ -21,7 +22,10 @@ struct Scratch {       // offsets inside the scratch region (which starts the wo
 };
 
 inline int64_t max_tiles_for(const allocmoe_layer_desc* d, int bm) {
-    return d->budget / bm + d->E;   // >= sum_e ceil(M_e / bm) for any split of B rows
+    // >= sum_e ceil(M_e / bm) for any split of B rows over the experts: an expert with
+    // rows has one tile plus one per further bm rows, and at most min(E, B) have rows
+    const int64_t active = std::min<int64_t>(d->E, d->budget);
+    return active + (d->budget - active) / bm;
 }
 
 Scratch scratch_of(const allocmoe_layer_desc* d) {
