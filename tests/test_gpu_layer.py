@@ -114,6 +114,12 @@ def test_deepseek_decode_full():
     layer = synth.make_layer(w)
     dev = check_layer(w, layer)                       # 0.5x budget: B = 96
     check_layer(w, layer, budget=192, dev=dev)        # original Top-6
+    del dev
+    for T, budget in ((1, 3), (5, 17)):               # a single token; a few tokens, ragged budget
+        wt = w.with_(T=T, budget=budget)
+        lt = dict(layer)
+        lt["X"] = layer["X"][:T].contiguous()
+        check_layer(wt, lt, tag=f"(T={T})")
 
 
 def test_qwen_shape_reduced_tokens():
