@@ -34,6 +34,9 @@ def parse_args():
                    choices=["decode", "prefill", "qwen", "olmoe", "stack"])
     p.add_argument("--budget-ratio", type=float, default=0.5,
                    help="layer budget as a fraction of T*K (the metric is quoted at 0.5)")
+    p.add_argument("--tokens", type=int, default=0,
+                   help="override the workload's token count T (budget = ratio*T*K): the step "
+                        "time against batch size")
     p.add_argument("--layers", type=int, default=26, help="layers of the stack workload")
     p.add_argument("--budgets", default="dirichlet",
                    choices=["dirichlet", "alloc-l", "ascending", "descending"],
@@ -56,7 +59,7 @@ def parse_args():
     return p.parse_args()
 
 
-def workload_for(name: str, ratio: float):
+def workload_for(name: str, ratio: float, tokens: int = 0):
     from paper_2604_08133_amd import synth
     if name == "decode":
         w = synth.deepseek_decode()
@@ -68,6 +71,8 @@ def workload_for(name: str, ratio: float):
         w = synth.olmoe()
     else:
         w = synth.deepseek_stack_layer(budget=0)
+    if tokens > 0:
+        w = w.with_(T=tokens)
     return w.with_(budget=int(round(ratio * w.T * w.K)))
 
 
@@ -150,7 +155,7 @@ def main():
         print(json.dumps({"copy_probe_bytes": n, "launches": 5}))
         return
 
-    w = workload_for(args.workload, args.budget_ratio)
+    w = workload_for(args.workload, args.budget_ratio, args.tokens)
     on_cpu = args.workload == "decode"
     # Inputs: generated on the CPU for the small workload (the oracle baseline
     # needs the same bytes), on the GPU for the big ones.  The stack workload is
@@ -229,18 +234,22 @@ def main():
     dom = "ffn1"
     dom_ms = stages[dom]
     targs = "<true, true>" if fp8 else "<true, false>"   # <SwiGLU half, 8-bit weights>
-    if args.workload == "decode":
-        kernel_name = "ffn_bf16_stream_kernel" + targs
+    # (the library moves the routed group to the tile kernel from 8 rows per expert on)
+    streaming = args.workload == "decode" if args.tokens <= 0 else pairs_sum < 8 * w.E * nL
+    # with --tokens the side of the roofline follows the arithmetic intensity of the launch
+    hbm_side = streaming or (args.tokens > 0 and
+                             ffn1_flops / ffn1_bytes * HBM_PEAK_GBS / 1e3 < MFMA_BF16_PEAK_TFLOPS)
+    kernel_name = ("ffn_bf16_stream_kernel" if streaming else "ffn_bf16_t256_kernel") + targs
+    if hbm_side:
         roof = {"bound": "hbm", "achieved": ffn1_bytes / (dom_ms * 1e-3) / 1e9,
                 "peak": HBM_PEAK_GBS, "unit": "GB/s"}
     else:
-        kernel_name = "ffn_bf16_t256_kernel" + targs
         roof = {"bound": "mfma", "achieved": ffn1_flops / (dom_ms * 1e-3) / 1e12,
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s"}
         # what the roofline allows at this arithmetic intensity: min(peak, flop/byte x HBM)
         roof["attainable"] = min(MFMA_BF16_PEAK_TFLOPS, ffn1_flops / ffn1_bytes * HBM_PEAK_GBS / 1e3)
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None if fp8 else traffic_from_profiles(args.workload, dom)
+    roof["traffic"] = None if fp8 or args.tokens > 0 else traffic_from_profiles(args.workload, dom)
     roof["kernel"] = kernel_name
     roof["kernel_ms"] = dom_ms / nL
     roof["launches_per_step"] = nL
