@@ -120,3 +120,34 @@ def test_budget_errors_reported_by_status():
         t = torch.zeros((8, 8), device=DEV)
         B.allocmoe_route_from_scores(desc, t, t, t, t)
     assert e.value.status == B.EBUDGET
+
+
+def test_seeded_random_cases():
+    # 400 seeded draws of (T, E, K, K_base, budget) and of the kind of score matrix:
+    # signed, few distinct levels (many ties), softmax-like, half zeros of both signs, all
+    # equal; mostly pools small enough for the direct ranking, one in five large
+    import random
+    rng = random.Random(5)
+    for n in range(400):
+        big = rng.random() < 0.2
+        T = rng.choice([100, 257, 700, 1500, 4096, 8192, 8200]) if big else rng.randint(1, 80)
+        E = rng.choice([1, 2, 3, 7, 16, 33, 64])
+        K = rng.randint(1, min(E, 16))
+        Kb = rng.randint(0, K)
+        budget = rng.randint(T * Kb, T * K)
+        kind = rng.choice(["signed", "levels", "softmax", "zeros", "equal"])
+        g = torch.Generator().manual_seed(rng.randint(1, 10**6))
+        if kind == "signed":
+            s = torch.randn((T, E), generator=g)
+        elif kind == "levels":
+            s = torch.randint(-3, 4, (T, E), generator=g).float() * 0.25
+        elif kind == "softmax":
+            s = torch.softmax(torch.randn((T, E), generator=g) * 2, dim=1)
+        elif kind == "zeros":
+            s = torch.randn((T, E), generator=g)
+            s[torch.rand((T, E), generator=g) < 0.5] = 0.0
+            s[torch.rand((T, E), generator=g) < 0.2] = -0.0
+        else:
+            s = torch.full((T, E), 0.125)
+        print(f"random case {n}: T={T} E={E} K={K} Kb={Kb} B={budget} {kind}", flush=True)
+        assert_same(gpu_route_dispatch(s, K, Kb, budget), oracle_route_dispatch(s, K, Kb, budget), n)
