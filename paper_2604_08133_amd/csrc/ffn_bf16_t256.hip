@@ -180,9 +180,8 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
     // holds the output of token row l%32 at column 8*(r/4) + 4*(l/32) + r%4, four
     // consecutive columns per register quad, which the epilogue stores as one 8-byte
     // word of bf16.
-    // step u of a loop pass
-    auto multiply = [&](const bf16x8 (&a)[NRB], int u) {
-        bf16x8 b[2];
+    // this wave's two weight fragments of step u of a loop pass
+    auto weights_of = [&](int u, bf16x8 (&b)[2]) {
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             if constexpr (FP8) {
@@ -193,6 +192,11 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
                 b[j] = __builtin_bit_cast(bf16x8, breg[u][j]);
             }
         }
+    };
+    // step u of a loop pass
+    auto multiply = [&](const bf16x8 (&a)[NRB], int u) {
+        bf16x8 b[2];
+        weights_of(u, b);
 #pragma unroll
         for (int i = 0; i < NRB; ++i) {
             acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[0], a[i], acc[i][0], 0, 0, 0);
@@ -200,12 +204,27 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
         }
     };
 
+    // the same, with the loads of activation slot `slot` (k step sl) between the MFMAs
+    auto multiply_and_issue = [&](const bf16x8 (&a)[NRB], int u, int sl, int slot) {
+        bf16x8 b[2];
+        weights_of(u, b);
+#pragma unroll
+        for (int i = 0; i < NRB; ++i) {
+            acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[0], a[i], acc[i][0], 0, 0, 0);
+            acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[1], a[i], acc[i][1], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            load_rows_to_lds(arow[i] + sl * (kStepK / 8), lds_wave + slot * kSlotBytes + i * 4096);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
     // Load schedule.  Per k16 step u (8 per loop pass = 2 slots): the step's MFMAs,
     // then 2 loads refilling its weight registers for step u + 8 (the compiler
-    // inserts the waits for those registers); after the third k16 of a slot
-    // additionally NRB loads refilling the slot used one step ago with the slot
-    // three ahead.  Slot s+1 is awaited after the third k16 of slot s: it was issued
-    // two slots earlier, followed by 2 + (6 + NRB + 2) + 6 loads    -> kWaitA.
+    // inserts the waits for those registers); after the barrier behind the third
+    // k16 of a slot additionally NRB loads refilling the slot used one step ago with
+    // the slot three ahead (issued between the MFMAs of the fourth k16, before that
+    // step's weight loads).  Slot s+1 is awaited after the third k16 of slot s: it
+    // was issued two slots earlier, followed by 2 + (6 + NRB + 2) + 6 loads -> kWaitA.
     // The prologue issues slot 0 and then exactly the sequence of one loop pass
     // (weights of steps 0-2, slot 1, steps 3-6, slot 2, step 7), so that count
     // holds from the first pass on.  Loads past the end of the contraction re-read
@@ -243,13 +262,22 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
                 read_a(s & 3, kc + 1, af[(u + 1) & 1]);
             else
                 read_a((s + 1) & 3, 0, af[(u + 1) & 1]);
-            multiply(af[u & 1], u);
+            if (kc == 3) {
+                // the loads of the slot three ahead (its predecessor was released by the
+                // barrier of the step before) go out between this step's MFMAs, one row
+                // block's after the two MFMAs of that row block: issued as one run behind
+                // the barrier they leave the matrix unit idle for ~40 instructions
+                const int sl = min(s + 3, KT - 1), slot = (s + 3) & 3;
+                multiply_and_issue(af[u & 1], u, sl, slot);
+            } else {
+                multiply(af[u & 1], u);
 #pragma unroll
-            for (int i = 0; i < NRB; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+                for (int i = 0; i < NRB; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+                }
+                __builtin_amdgcn_sched_group_barrier(0x008, NRB, 0);     // the remaining MFMAs
             }
-            __builtin_amdgcn_sched_group_barrier(0x008, NRB, 0);     // the remaining MFMAs
             __builtin_amdgcn_sched_barrier(0);
             if constexpr (!FP8)
                 load_b(4 * s2 + u + kBRing, u);
@@ -260,7 +288,6 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
                 // everybody's has, and everybody is done with the slot before this one
                 wait_vmcnt_le<kWaitA>();
                 wg_barrier_nofence();
-                issue_a(min(s + 3, KT - 1), (s + 3) & 3);
             }
         }
     };
