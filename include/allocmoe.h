@@ -191,7 +191,9 @@ allocmoe_status allocmoe_route_from_scores(const allocmoe_layer_desc *desc, cons
  * expert_offsets i32 [E+1] (rows of expert e are offsets[e]..offsets[e+1]),
  * row_token / row_rank i32 [budget] (the pair behind each row), inv_row i32
  * [T,K] (row of pair (t,j), -1 if not kept).  sum_t keep_count[t] must equal
- * desc->budget (not checked: it lives on the device). */
+ * desc->budget (it lives on the device and is not checked on the host).  If it is
+ * larger, nothing is written past the budget: pairs whose row would be >= budget get
+ * inv_row -1 and no row, and every expert_offsets entry is capped at budget. */
 allocmoe_status allocmoe_dispatch(const allocmoe_layer_desc *desc, const int32_t *topk_ids,
                                   const int32_t *keep_count, int32_t *expert_offsets,
                                   int32_t *row_token, int32_t *row_rank, int32_t *inv_row,
@@ -205,7 +207,9 @@ allocmoe_status allocmoe_dispatch(const allocmoe_layer_desc *desc, const int32_t
  * calls with a shared expert the library runs that expert's GEMMs on a
  * stream of its own (one extra stream and two events per device, created on
  * first use, default priority) beside the selection; both ends are tied to
- * `stream` with events, no host synchronisation.  The call only enqueues kernels
+ * `stream` with events, no host synchronisation.  Calls on one device from
+ * several host threads are serialised by a per-device lock for the duration of
+ * the enqueue (they share that stream and its events).  The call only enqueues kernels
  * and those two events (no allocation, no memset, no host wait), so it may be
  * captured into a HIP graph and replayed; make the first call on a device outside
  * a capture (it creates the side stream). */
@@ -213,27 +217,63 @@ allocmoe_status allocmoe_moe_forward(const allocmoe_layer_desc *desc, const void
                                      const allocmoe_weights *w, void *Y, void *ws,
                                      size_t ws_bytes, allocmoe_stream stream);
 
-/* Stages of allocmoe_moe_forward, in launch order. */
+/* Intervals reported by allocmoe_moe_forward_timed (indices into stage_ms). */
 typedef enum {
     ALLOCMOE_STAGE_ROUTE = 0,   /* steps 1-2: gate, softmax, sorted candidates              */
     ALLOCMOE_STAGE_PLAN = 1,    /* steps 3-4: Alloc-T selection, dispatch, tile map          */
-    ALLOCMOE_STAGE_FFN1 = 2,    /* step 5: H = silu(x W1) * (x W3), selected rows + shared   */
-    ALLOCMOE_STAGE_FFN2 = 3,    /* step 5: O = H W2, selected rows + shared                  */
+    ALLOCMOE_STAGE_FFN1 = 2,    /* step 5 on `stream`: H = silu(x W1) * (x W3); the selected */
+                                /* rows, and the shared expert where it shares the launch    */
+    ALLOCMOE_STAGE_FFN2 = 3,    /* step 5 on `stream`: O = H W2; then the wait for the       */
+                                /* library's own stream, if it was used                      */
     ALLOCMOE_STAGE_COMBINE = 4, /* step 6: Eq. (2)                                           */
-    ALLOCMOE_N_STAGES = 5
+    ALLOCMOE_STAGE_SHARED_FFN1 = 5, /* the shared expert's first GEMM on the library's stream */
+    ALLOCMOE_STAGE_SHARED_FFN2 = 6, /* its second GEMM there (both 0 if that stream was idle) */
+    ALLOCMOE_STAGE_EXPERT_SPAN = 7, /* start of PLAN to start of COMBINE: the region in which */
+                                /* every expert GEMM of the layer runs, on either stream     */
+    ALLOCMOE_STAGE_TOTAL = 8,   /* start of ROUTE to the end of COMBINE                      */
+    ALLOCMOE_N_STAGES = 9
 } allocmoe_stage;
 
-/* Measurement variant of allocmoe_moe_forward: same work and same kernels, but
- * every stage runs on `stream` alone, one after the other (the shared expert's
- * first GEMM shares a launch with the routed experts' instead of running beside
- * the selection), and a HIP event is recorded on the stream around every stage; the call then WAITS for the last event (the one exception to the
- * no-synchronisation rule) and writes the stage durations in milliseconds to
- * stage_ms[ALLOCMOE_N_STAGES] (host memory).  The events are host objects the
- * library creates on first use and keeps; not thread-safe; for benchmarking. */
+/* Measurement variant of allocmoe_moe_forward: the same kernels in the same launch
+ * structure (the shared expert on the library's own stream where allocmoe_moe_forward
+ * puts it there), with a HIP event recorded on the stream concerned around every
+ * launch; the call then WAITS for the last events (the one exception to the
+ * no-synchronisation rule) and writes the durations in milliseconds to
+ * stage_ms[ALLOCMOE_N_STAGES] (host memory).  Intervals of kernels that run beside each
+ * other on the two streams overlap in time: EXPERT_SPAN is the wall-clock figure for
+ * them.  The events are host objects the library creates per device on first use and
+ * keeps.  For benchmarking. */
 allocmoe_status allocmoe_moe_forward_timed(const allocmoe_layer_desc *desc, const void *X,
                                            const allocmoe_weights *w, void *Y, void *ws,
                                            size_t ws_bytes, allocmoe_stream stream,
                                            float *stage_ms);
+
+/* Ceiling probes (measurement utilities, not on the layer's path; both WAIT for their
+ * kernels and copy a few bytes back).  The rooflines of the layer's kernels are quoted
+ * against the published peaks; these re-measure what the device at hand sustains.
+ *
+ * allocmoe_probe_mfma: the matrix-core instruction the expert GEMMs use
+ * (32x32x16 bf16, fp32 accumulate) issued back to back on eight independent
+ * accumulators per wave, `waves_per_simd` (1 or 2) waves on every SIMD of every compute
+ * unit (a grid of 256 workgroups), `iters` passes of 8 instructions.  The operand
+ * fragments come from `operands` (device, allocmoe_probe_mfma_operand_bytes() bytes of
+ * bf16, 16-byte aligned, filled by the caller: zeros or random values - the clock the
+ * device sustains, and so the rate, depends on the data).  Writes the achieved TFLOP/s
+ * and the shader clock in MHz (core-clock counter against the constant 100 MHz counter
+ * around the loop).  sink: device scratch of allocmoe_probe_sink_bytes() bytes.
+ *
+ * allocmoe_probe_hbm_read: reads `bytes` (a multiple of 256 KiB is used) of `buf` with
+ * 16-byte loads per lane, eight in flight, `repeats` times, with (1) or without (0) the
+ * non-temporal hint; writes the achieved GB/s.  Use a buffer much larger than the
+ * 256 MiB memory-side cache. */
+size_t allocmoe_probe_mfma_operand_bytes(void);
+size_t allocmoe_probe_sink_bytes(void);
+allocmoe_status allocmoe_probe_mfma(const void *operands, size_t operand_bytes,
+                                    int waves_per_simd, int iters, void *sink, size_t sink_bytes,
+                                    float *tflops, float *shader_mhz, allocmoe_stream stream);
+allocmoe_status allocmoe_probe_hbm_read(const void *buf, size_t bytes, int nontemporal,
+                                        int repeats, void *sink, size_t sink_bytes,
+                                        float *gbytes_per_s, allocmoe_stream stream);
 
 /* Summary numbers of allocmoe_routing_stats (device memory, 5 floats in this order). */
 typedef struct {

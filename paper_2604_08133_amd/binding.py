@@ -23,9 +23,14 @@ EXPORTS = [
     "allocmoe_pack_weights", "allocmoe_route", "allocmoe_route_from_scores",
     "allocmoe_dispatch", "allocmoe_moe_forward", "allocmoe_moe_forward_timed",
     "allocmoe_alloc_l", "allocmoe_layer_schedule", "allocmoe_routing_stats",
+    "allocmoe_probe_mfma_operand_bytes", "allocmoe_probe_sink_bytes", "allocmoe_probe_mfma",
+    "allocmoe_probe_hbm_read",
     "allocmoe_status_string",
 ]
-STAGES = ["route", "plan", "ffn1", "ffn2", "combine"]
+# intervals of allocmoe_moe_forward_timed (include/allocmoe.h, allocmoe_stage)
+STAGES = ["route", "plan", "ffn1", "ffn2", "combine", "shared_ffn1", "shared_ffn2", "expert_span",
+          "total"]
+_SIZE_T_EXPORTS = ("allocmoe_probe_mfma_operand_bytes", "allocmoe_probe_sink_bytes")
 
 
 class LayerDesc(ctypes.Structure):
@@ -69,7 +74,9 @@ def load() -> ctypes.CDLL:
         lib.allocmoe_status_string.restype = ctypes.c_char_p
         lib.allocmoe_status_string.argtypes = [ctypes.c_int]
         for name in EXPORTS:
-            if name != "allocmoe_status_string":
+            if name in _SIZE_T_EXPORTS:
+                getattr(lib, name).restype = ctypes.c_size_t
+            elif name != "allocmoe_status_string":
                 getattr(lib, name).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -191,6 +198,32 @@ def allocmoe_moe_forward_timed(desc: LayerDesc, X, w: Weights, Y, ws: torch.Tens
                                              ctypes.c_size_t(ws.numel() * ws.element_size()),
                                              _stream(stream), ms), "allocmoe_moe_forward_timed")
     return list(ms)
+
+
+def allocmoe_probe_mfma(operands: torch.Tensor, waves_per_simd: int, iters: int,
+                        sink: torch.Tensor, stream=None):
+    """Returns (TFLOP/s, shader clock in MHz) of the matrix-core issue loop; synchronises."""
+    tf, mhz = ctypes.c_float(0), ctypes.c_float(0)
+    _check(load().allocmoe_probe_mfma(_ptr(operands),
+                                      ctypes.c_size_t(operands.numel() * operands.element_size()),
+                                      ctypes.c_int(waves_per_simd), ctypes.c_int(iters), _ptr(sink),
+                                      ctypes.c_size_t(sink.numel() * sink.element_size()),
+                                      ctypes.byref(tf), ctypes.byref(mhz), _stream(stream)),
+           "allocmoe_probe_mfma")
+    return tf.value, mhz.value
+
+
+def allocmoe_probe_hbm_read(buf: torch.Tensor, nontemporal: bool, repeats: int,
+                            sink: torch.Tensor, stream=None) -> float:
+    """Returns the achieved GB/s of the streaming read; synchronises."""
+    gbs = ctypes.c_float(0)
+    _check(load().allocmoe_probe_hbm_read(_ptr(buf), ctypes.c_size_t(buf.numel() * buf.element_size()),
+                                          ctypes.c_int(1 if nontemporal else 0),
+                                          ctypes.c_int(repeats), _ptr(sink),
+                                          ctypes.c_size_t(sink.numel() * sink.element_size()),
+                                          ctypes.byref(gbs), _stream(stream)),
+           "allocmoe_probe_hbm_read")
+    return gbs.value
 
 
 METRICS = ["spearman_load", "entropy_orig", "entropy_kept", "js_divergence", "spearman_tokens"]

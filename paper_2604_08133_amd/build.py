@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liballocmoe.so")
 SOURCES = ["api.hip", "route.hip", "plan.hip", "pack.hip", "ffn_f32.hip", "ffn_bf16.hip", "ffn_bf16_t256.hip",
-           "combine.hip", "stats.hip", "alloc_l.cpp"]
+           "combine.hip", "stats.hip", "probes.hip", "alloc_l.cpp"]
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
                "-Wall", "-Wno-inline-asm", "-Wno-unused-command-line-argument", "-Wno-unknown-attributes"]

@@ -354,61 +354,82 @@ allocmoe_status allocmoe_routing_stats(const allocmoe_layer_desc* desc, const fl
 
 namespace {
 
-// Host-side objects for running the shared expert's first GEMM beside the
-// selection: one extra stream (default priority, not synchronising with the
-// null stream) and two events without timing per device, created on first use
-// and kept for the life of the process.
-struct SideStream {
-    hipStream_t stream = nullptr;
+// Host-side objects the library keeps per device, created on first use and kept for
+// the life of the process: one extra stream (default priority, not synchronising with
+// the null stream) and two events without timing, for running the shared expert's GEMMs
+// beside the selection; the timing events of the measurement variant.  `lock` is held
+// for the whole enqueue sequence of a forward call, so that two host threads calling on
+// one device cannot interleave their records and waits on the shared events.
+constexpr int kTimedEvents = 9;   // main stream: before each of the 5 stages + end; side stream: 3
+struct DeviceState {
+    std::mutex lock;
+    hipStream_t side = nullptr;
     hipEvent_t fork = nullptr, join = nullptr;
+    hipEvent_t ev[kTimedEvents] = {};
+    bool have_ev = false;
 };
 
-allocmoe_status side_stream_of_current_device(SideStream** out) {
+
+allocmoe_status device_state_of_current_device(DeviceState** out) {
     constexpr int kMaxDevices = 64;
-    static SideStream table[kMaxDevices];
-    static std::mutex lock;
+    static DeviceState table[kMaxDevices];
     int dev = 0;
     ALLOCMOE_TRY(hipGetDevice(&dev));
     if (dev < 0 || dev >= kMaxDevices) return ALLOCMOE_EHIP;
-    std::lock_guard<std::mutex> guard(lock);
-    SideStream& s = table[dev];
-    if (s.stream == nullptr) {
-        hipStream_t st = nullptr;
-        ALLOCMOE_TRY(hipStreamCreateWithFlags(&st, hipStreamNonBlocking));
-        ALLOCMOE_TRY(hipEventCreateWithFlags(&s.fork, hipEventDisableTiming));
-        ALLOCMOE_TRY(hipEventCreateWithFlags(&s.join, hipEventDisableTiming));
-        s.stream = st;
-    }
-    *out = &s;
+    *out = &table[dev];
     return ALLOCMOE_OK;
 }
 
-// Records ev[i] (when ev is not null) on the stream before stage i.
-#define ALLOCMOE_MARK(i)                                                  \
-    do {                                                                  \
-        if (ev != nullptr) ALLOCMOE_TRY(hipEventRecord(ev[i], stream));   \
-    } while (0)
+// (state.lock held)
+allocmoe_status ensure_side_stream(DeviceState& s) {
+    if (s.side != nullptr) return ALLOCMOE_OK;
+    hipStream_t st = nullptr;
+    ALLOCMOE_TRY(hipStreamCreateWithFlags(&st, hipStreamNonBlocking));
+    ALLOCMOE_TRY(hipEventCreateWithFlags(&s.fork, hipEventDisableTiming));
+    ALLOCMOE_TRY(hipEventCreateWithFlags(&s.join, hipEventDisableTiming));
+    s.side = st;
+    return ALLOCMOE_OK;
+}
 
-allocmoe_status forward_impl(const allocmoe_layer_desc* desc, const void* X,
-                             const allocmoe_weights* w, void* Y, void* ws, size_t ws_bytes,
-                             allocmoe_stream stream_, hipEvent_t* ev) {
-    allocmoe_ws_layout L;
-    const allocmoe_status st = layout_of(desc, &L);
+// Records ev[i] (when ev is not null) on a stream.
+#define ALLOCMOE_MARK_ON(i, st)                                          \
+    do {                                                                 \
+        if (ev != nullptr) ALLOCMOE_TRY(hipEventRecord(ev[i], st));      \
+    } while (0)
+#define ALLOCMOE_MARK(i) ALLOCMOE_MARK_ON(i, stream)
+// indices of the side-stream events
+constexpr int kEvSide0 = 6, kEvSide1 = 7, kEvSide2 = 8;
+
+// Host-side argument checks of the forward entry points (nothing is enqueued and no
+// HIP call is made before they pass).
+allocmoe_status validate_forward(const allocmoe_layer_desc* desc, const void* X,
+                                 const allocmoe_weights* w, const void* Y, const void* ws,
+                                 size_t ws_bytes, allocmoe_ws_layout* L) {
+    const allocmoe_status st = layout_of(desc, L);
     if (st != ALLOCMOE_OK) return st;
     if (!X || !Y || !w || !w->Wg) return ALLOCMOE_EINVAL;
-    const bool bf16 = desc->dtype == ALLOCMOE_BF16;
-    const int Is = desc->I_shared;
-    if (bf16) {
+    if (desc->dtype == ALLOCMOE_BF16) {
         if (!w->packed || !aligned(w->packed, kAlign)) return ALLOCMOE_EINVAL;
-        // rows are read and written in 16-byte pieces
-        if (!aligned(X, 16) || !aligned(Y, 16)) return ALLOCMOE_EINVAL;
     } else {
         if (!w->W1 || !w->W3 || !w->W2) return ALLOCMOE_EINVAL;
-        if (Is && (!w->Ws1 || !w->Ws3 || !w->Ws2)) return ALLOCMOE_EINVAL;
+        if (desc->I_shared && (!w->Ws1 || !w->Ws3 || !w->Ws2)) return ALLOCMOE_EINVAL;
     }
     if (desc->shared_gate && !w->w_sg) return ALLOCMOE_EINVAL;
-    if (ws == nullptr || ws_bytes < L.total || !aligned(ws, kAlign)) return ALLOCMOE_EWORKSPACE;
+    if (ws == nullptr || ws_bytes < L->total || !aligned(ws, kAlign)) return ALLOCMOE_EWORKSPACE;
+    // rows are read and written in 16-byte pieces
     if (!aligned(X, 16) || !aligned(Y, 16)) return ALLOCMOE_EINVAL;
+    return ALLOCMOE_OK;
+}
+
+// (state.lock held)
+allocmoe_status forward_impl(const allocmoe_layer_desc* desc, const void* X,
+                             const allocmoe_weights* w, void* Y, void* ws, size_t ws_bytes,
+                             allocmoe_stream stream_, DeviceState& state, hipEvent_t* ev) {
+    allocmoe_ws_layout L;
+    const allocmoe_status st = validate_forward(desc, X, w, Y, ws, ws_bytes, &L);
+    if (st != ALLOCMOE_OK) return st;
+    const bool bf16 = desc->dtype == ALLOCMOE_BF16;
+    const int Is = desc->I_shared;
 
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     const int T = desc->T, d = desc->d, E = desc->E, I = desc->I, K = desc->K;
@@ -454,10 +475,9 @@ allocmoe_status forward_impl(const allocmoe_layer_desc* desc, const void* X,
     // single-workgroup plan kernel is enqueued first, so that it gets a compute unit
     // at once.  Decode shapes (both groups on the weight-streaming kernel) keep one
     // stream and one launch per half for both groups: there the two event waits of a
-    // fork and join cost more than the overlap gains.  The measurement variant
-    // (ev != null) keeps every stage on the caller's stream.
-    const bool overlap = ev == nullptr && bf16 && Is > 0 && B > 0 && (routed_tiled || shared_tiled);
-    SideStream* side = nullptr;
+    // fork and join cost more than the overlap gains.
+    const bool overlap = bf16 && Is > 0 && B > 0 && (routed_tiled || shared_tiled);
+    struct { hipStream_t stream; hipEvent_t fork, join; } side_{}, *side = &side_;
     StreamGroup s1, s2;   // the shared expert's two GEMMs
     if (bf16 && Is) {
         const PackedLayout p = packed_of(desc);
@@ -480,15 +500,20 @@ allocmoe_status forward_impl(const allocmoe_layer_desc* desc, const void* X,
         ALLOCMOE_TRY(hipStreamWaitEvent(side->stream, side->fork, 0));
         for (int half = 0; half < 2; ++half) {
             const StreamGroup& sh = half == 0 ? s1 : s2;
+            ALLOCMOE_MARK_ON(half == 0 ? kEvSide0 : kEvSide1, side->stream);
             ALLOCMOE_TRY(shared_tiled ? launch_ffn_bf16_t256(half == 0, none, sh, side->stream)
                                       : launch_ffn_bf16_stream(half == 0, sh, none, side->stream));
         }
+        ALLOCMOE_MARK_ON(kEvSide2, side->stream);
         ALLOCMOE_TRY(hipEventRecord(side->join, side->stream));
         return ALLOCMOE_OK;
     };
     if (overlap) {
-        const allocmoe_status sst = side_stream_of_current_device(&side);
+        const allocmoe_status sst = ensure_side_stream(state);
         if (sst != ALLOCMOE_OK) return sst;
+        side_.stream = state.side;
+        side_.fork = state.fork;
+        side_.join = state.join;
         if (!shared_tiled) {
             const allocmoe_status fst = fork_shared_expert();
             if (fst != ALLOCMOE_OK) return fst;
@@ -523,8 +548,11 @@ allocmoe_status forward_impl(const allocmoe_layer_desc* desc, const void* X,
                              at<uint64_t>(scr, s.words), at<int32_t>(scr, s.prefix), bm, tile_info,
                              stream));
     if (overlap && shared_tiled) {
-        for (int half = 0; half < 2; ++half)
+        for (int half = 0; half < 2; ++half) {
+            ALLOCMOE_MARK_ON(half == 0 ? kEvSide0 : kEvSide1, side->stream);
             ALLOCMOE_TRY(launch_ffn_bf16_t256(half == 0, none, half == 0 ? s1 : s2, side->stream));
+        }
+        ALLOCMOE_MARK_ON(kEvSide2, side->stream);
         ALLOCMOE_TRY(hipEventRecord(side->join, side->stream));
     }
     // step 5: expert networks over the selected rows, then the shared expert
@@ -592,7 +620,9 @@ allocmoe_status forward_impl(const allocmoe_layer_desc* desc, const void* X,
     ALLOCMOE_MARK(ALLOCMOE_STAGE_COMBINE);
     ALLOCMOE_TRY(launch_combine(desc->dtype, O, Os, inv_row, topk_s, keep_count, sgate, T, d, K, Y,
                                 stream));
-    ALLOCMOE_MARK(ALLOCMOE_N_STAGES);
+    ALLOCMOE_MARK(5);
+    if (ev != nullptr && !overlap)   // nothing ran beside the caller's stream: empty intervals
+        for (int i = kEvSide0; i <= kEvSide2; ++i) ALLOCMOE_MARK(i);
     return ALLOCMOE_OK;
 }
 
@@ -603,7 +633,14 @@ extern "C" {
 allocmoe_status allocmoe_moe_forward(const allocmoe_layer_desc* desc, const void* X,
                                      const allocmoe_weights* w, void* Y, void* ws,
                                      size_t ws_bytes, allocmoe_stream stream) {
-    return forward_impl(desc, X, w, Y, ws, ws_bytes, stream, nullptr);
+    allocmoe_ws_layout L;
+    const allocmoe_status vst = validate_forward(desc, X, w, Y, ws, ws_bytes, &L);
+    if (vst != ALLOCMOE_OK) return vst;
+    DeviceState* state = nullptr;
+    const allocmoe_status st = device_state_of_current_device(&state);
+    if (st != ALLOCMOE_OK) return st;
+    std::lock_guard<std::mutex> guard(state->lock);
+    return forward_impl(desc, X, w, Y, ws, ws_bytes, stream, *state, nullptr);
 }
 
 allocmoe_status allocmoe_moe_forward_timed(const allocmoe_layer_desc* desc, const void* X,
@@ -611,18 +648,29 @@ allocmoe_status allocmoe_moe_forward_timed(const allocmoe_layer_desc* desc, cons
                                            size_t ws_bytes, allocmoe_stream stream,
                                            float* stage_ms) {
     if (stage_ms == nullptr) return ALLOCMOE_EINVAL;
-    // events are host-side objects, created once per process and reused
-    static hipEvent_t ev[ALLOCMOE_N_STAGES + 1];
-    static bool have_events = false;
-    if (!have_events) {
-        for (int i = 0; i <= ALLOCMOE_N_STAGES; ++i) ALLOCMOE_TRY(hipEventCreate(&ev[i]));
-        have_events = true;
+    allocmoe_ws_layout L;
+    const allocmoe_status vst = validate_forward(desc, X, w, Y, ws, ws_bytes, &L);
+    if (vst != ALLOCMOE_OK) return vst;
+    DeviceState* state = nullptr;
+    const allocmoe_status dst = device_state_of_current_device(&state);
+    if (dst != ALLOCMOE_OK) return dst;
+    std::lock_guard<std::mutex> guard(state->lock);
+    if (!state->have_ev) {
+        for (int i = 0; i < kTimedEvents; ++i) ALLOCMOE_TRY(hipEventCreate(&state->ev[i]));
+        state->have_ev = true;
     }
-    const allocmoe_status st = forward_impl(desc, X, w, Y, ws, ws_bytes, stream, ev);
+    hipEvent_t* ev = state->ev;
+    const allocmoe_status st = forward_impl(desc, X, w, Y, ws, ws_bytes, stream, *state, ev);
     if (st != ALLOCMOE_OK) return st;
-    ALLOCMOE_TRY(hipEventSynchronize(ev[ALLOCMOE_N_STAGES]));
-    for (int i = 0; i < ALLOCMOE_N_STAGES; ++i)
-        ALLOCMOE_TRY(hipEventElapsedTime(&stage_ms[i], ev[i], ev[i + 1]));
+    // (the end mark of the caller's stream follows the join with the side stream)
+    ALLOCMOE_TRY(hipEventSynchronize(ev[5]));
+    ALLOCMOE_TRY(hipEventSynchronize(ev[kEvSide2]));
+    for (int i = 0; i < 5; ++i) ALLOCMOE_TRY(hipEventElapsedTime(&stage_ms[i], ev[i], ev[i + 1]));
+    ALLOCMOE_TRY(hipEventElapsedTime(&stage_ms[ALLOCMOE_STAGE_SHARED_FFN1], ev[kEvSide0], ev[kEvSide1]));
+    ALLOCMOE_TRY(hipEventElapsedTime(&stage_ms[ALLOCMOE_STAGE_SHARED_FFN2], ev[kEvSide1], ev[kEvSide2]));
+    ALLOCMOE_TRY(hipEventElapsedTime(&stage_ms[ALLOCMOE_STAGE_EXPERT_SPAN], ev[ALLOCMOE_STAGE_PLAN],
+                                     ev[ALLOCMOE_STAGE_COMBINE]));
+    ALLOCMOE_TRY(hipEventElapsedTime(&stage_ms[ALLOCMOE_STAGE_TOTAL], ev[0], ev[5]));
     return ALLOCMOE_OK;
 }
 

@@ -3,7 +3,9 @@
 // (no renormalisation), plus the always-on shared expert's output times its
 // gate.  A gather: one workgroup per token walks the token's kept ranks in
 // order j = 0, 1, ... and adds s[t,j] * O[inv_row[t,j], :] in fp32, then the
-// shared term, then rounds once to the output type.
+// shared term, then rounds once to the output type.  A kept rank without a row
+// (inv_row < 0: only possible when a caller hands the dispatch keep counts that sum
+// to more than the budget) contributes nothing.
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -50,7 +52,8 @@ __global__ __launch_bounds__(256) void combine_kernel(
                     acc[2 * i + 1] += wgt * __uint_as_float(w[i] & 0xFFFF0000u);
                 }
             };
-            for (int j = 0; j < kt; ++j) add(O + static_cast<size_t>(rows[j]) * d, wts[j]);
+            for (int j = 0; j < kt; ++j)
+                if (rows[j] >= 0) add(O + static_cast<size_t>(rows[j]) * d, wts[j]);
             if (Os) add(Os + static_cast<size_t>(t) * d, g);
             uint32_t w[4];
 #pragma unroll
@@ -63,6 +66,7 @@ __global__ __launch_bounds__(256) void combine_kernel(
         for (int c = threadIdx.x * 4; c < d; c += blockDim.x * 4) {
             float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
             for (int j = 0; j < kt; ++j) {
+                if (rows[j] < 0) continue;
                 const float4 o = load4(O + static_cast<size_t>(rows[j]) * d + c);
                 acc.x += wts[j] * o.x;
                 acc.y += wts[j] * o.y;
@@ -81,7 +85,8 @@ __global__ __launch_bounds__(256) void combine_kernel(
     } else {
         for (int c = threadIdx.x; c < d; c += blockDim.x) {
             float acc = 0.f;
-            for (int j = 0; j < kt; ++j) acc += wts[j] * load_f32(O, static_cast<size_t>(rows[j]) * d + c);
+            for (int j = 0; j < kt; ++j)
+                if (rows[j] >= 0) acc += wts[j] * load_f32(O, static_cast<size_t>(rows[j]) * d + c);
             if (Os) acc += g * load_f32(Os, static_cast<size_t>(t) * d + c);
             store_elem(Y, static_cast<size_t>(t) * d + c, acc);
         }

@@ -83,17 +83,6 @@ __device__ __forceinline__ void wait_vmcnt_le() {
     __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
-#ifdef ALLOCMOE_TRACE
-__device__ long long t256_phase[2][1 << 14][4];
-#define ALLOCMOE_T256_PHASE(i)                                                              \
-    do {                                                                                    \
-        if (threadIdx.x == 0 && blockIdx.x < (1 << 14))                                     \
-            t256_phase[SWIGLU ? 0 : 1][blockIdx.x][i] = clock64();                           \
-    } while (0)
-#else
-#define ALLOCMOE_T256_PHASE(i)
-#endif
-
 // 8 E4M3 codes (byte i = element i) -> 8 bf16 values, exactly
 __device__ __forceinline__ bf16x8 widen_fp8x8(uint2 q) {
     typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -116,7 +105,6 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
                                           const void* b1, const float* sc0, const float* sc1,
                                           int KT, int wave, int lane, int row0,
                                           int rows, int nt, void* C, int ldc) {
-    ALLOCMOE_T256_PHASE(0);
     f32x16 acc[NRB][2];
 #pragma unroll
     for (int i = 0; i < NRB; ++i)
@@ -247,7 +235,6 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
     wg_barrier_nofence();
     bf16x8 af[2][NRB];
     read_a(0, 0, af[0]);
-    ALLOCMOE_T256_PHASE(1);
 
     // steps [4 s2, 4 s2 + STEPS) of the contraction
     auto pass = [&](int s2, auto steps_const) {
@@ -297,7 +284,6 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
     if (kPass == 16 && s2 < KT) pass(s2, std::integral_constant<int, 8>{});
     __builtin_amdgcn_sched_barrier(0);
     wait_vmcnt_le<0>();   // the surplus loads have landed before registers and LDS are reused
-    ALLOCMOE_T256_PHASE(2);
 
     // epilogue: lane l owns token row l%32 of every row block; register quad g of
     // fragment j holds columns 32 j + 8 g + 4 (l/32) .. + 3 of the wave's columns.
@@ -347,12 +333,7 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
                 }
         }
     }
-    ALLOCMOE_T256_PHASE(3);
 }
-
-#ifdef ALLOCMOE_TRACE
-__device__ long long t256_trace[2][1 << 14][4];
-#endif
 
 template <bool SWIGLU, bool FP8>
 __global__ __launch_bounds__(kWaves* kWave, 1) void ffn_bf16_t256_kernel(StreamGroup g0,
@@ -431,9 +412,6 @@ __global__ __launch_bounds__(kWaves* kWave, 1) void ffn_bf16_t256_kernel(StreamG
     const int lane = lane_id(), wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int n_rb = (rows + 31) / 32;   // 32-row blocks that hold real rows
     const int KT = Kd / kStepK;
-#ifdef ALLOCMOE_TRACE
-    const long long trace_t0 = wall_clock64(), trace_c0 = clock64();
-#endif
 
     // B: the two fragment streams of this wave's 64 weight columns; a stream is
     // Kd/16 fragments of 64 lanes x 16 B (FP8: Kd/32), contiguous
@@ -474,31 +452,9 @@ __global__ __launch_bounds__(kWaves* kWave, 1) void ffn_bf16_t256_kernel(StreamG
         default: ALLOCMOE_T256_CASE(8)
     }
 #undef ALLOCMOE_T256_CASE
-#ifdef ALLOCMOE_TRACE
-    if (threadIdx.x == 0 && blockIdx.x < (1 << 14)) {
-        long long* t = t256_trace[SWIGLU ? 0 : 1][blockIdx.x];
-        t[0] = trace_t0;
-        t[1] = wall_clock64();
-        t[2] = (first ? 1 : 0) | (n_rb << 4) | (nt << 8) | (tile << 16) | ((clock64() - trace_c0) << 32);
-        t[3] = __builtin_amdgcn_s_getreg(63492) | (static_cast<long long>(__builtin_amdgcn_s_getreg(63508)) << 32);
-    }
-#endif
 }
 
 }  // namespace
-
-#ifdef ALLOCMOE_TRACE
-extern "C" int allocmoe_debug_t256_phase(long long* host_out, int n_rows) {
-    return static_cast<int>(hipMemcpyFromSymbol(host_out, HIP_SYMBOL(t256_phase),
-                                                sizeof(long long) * 4 * n_rows, 0,
-                                                hipMemcpyDeviceToHost));
-}
-extern "C" int allocmoe_debug_t256_trace(long long* host_out, int n_rows) {
-    return static_cast<int>(hipMemcpyFromSymbol(host_out, HIP_SYMBOL(t256_trace),
-                                                sizeof(long long) * 4 * n_rows, 0,
-                                                hipMemcpyDeviceToHost));
-}
-#endif
 
 // Rows per tile of a dense group (every row tile reads the same weights): full
 // 256-row tiles where those fill the chip; with fewer tokens the smallest multiple of

@@ -240,7 +240,8 @@ __device__ void dispatch_phase(PlanShared& sh, const int32_t* topk_ids,
         }
         __threadfence_block();
         __syncthreads();
-        if (tid <= E) expert_offsets[tid] = sh.expert_off[tid];
+        // (offsets past the budget can only come from keep counts that sum to more than it)
+        if (tid <= E) expert_offsets[tid] = min(sh.expert_off[tid], static_cast<int32_t>(max_rows));
     }
 
     // ---- C: place every pair
@@ -258,6 +259,8 @@ __device__ void dispatch_phase(PlanShared& sh, const int32_t* topk_ids,
                 if (row < max_rows) {   // holds whenever sum_t keep_count[t] <= budget
                     row_token[row] = t;
                     row_rank[row] = j;
+                } else {
+                    row = -1;           // no row behind this pair: the combine skips it
                 }
             }
             inv_row[static_cast<size_t>(t) * K + j] = row;
@@ -268,11 +271,12 @@ __device__ void dispatch_phase(PlanShared& sh, const int32_t* topk_ids,
 // Tile map of the grouped GEMMs (layout and order: kernels.hpp), written by the
 // first wave of the workgroup.  expert_off: the E+1 row offsets (LDS).
 __device__ __forceinline__ void write_tile_map(const int32_t* expert_off, int E, int bm,
-                                               int32_t* __restrict__ tile_info) {
+                                               int32_t* __restrict__ tile_info, int max_rows) {
     const int lane = lane_id();
-    // lane = expert: its rows in n tiles of rt rows (the last one may hold fewer)
-    int rows = lane < E ? expert_off[lane + 1] - expert_off[lane] : 0;
-    int off = lane < E ? expert_off[lane] : 0;
+    // lane = expert: its rows in n tiles of rt rows (the last one may hold fewer); rows past
+    // the budget (keep counts that sum to more than it) do not exist
+    int off = lane < E ? min(expert_off[lane], max_rows) : 0;
+    int rows = lane < E ? min(expert_off[lane + 1], max_rows) - off : 0;
     int n = (rows + bm - 1) / bm;
     int rt = n > 0 ? (rows + n - 1) / n : 0;
     // rank of the expert by (rows per tile descending, expert ascending)
@@ -302,8 +306,9 @@ __device__ __forceinline__ void write_tile_map(const int32_t* expert_off, int E,
     if (lane == kWave - 1) tile_info[0] = incl;
 }
 
-__device__ void tilemap_phase(PlanShared& sh, int E, int bm, int32_t* __restrict__ tile_info) {
-    if (threadIdx.x < kWave) write_tile_map(sh.expert_off, E, bm, tile_info);
+__device__ void tilemap_phase(PlanShared& sh, int E, int bm, int32_t* __restrict__ tile_info,
+                              int max_rows) {
+    if (threadIdx.x < kWave) write_tile_map(sh.expert_off, E, bm, tile_info, max_rows);
 }
 
 // ---------------------------------------------------------------------------
@@ -371,16 +376,6 @@ __device__ __forceinline__ uint64_t wave_transpose64(uint64_t x) {
     return x;
 }
 
-#ifdef ALLOCMOE_TRACE
-__device__ long long plan_trace[16];
-#define ALLOCMOE_PLAN_STAMP(i)                                   \
-    do {                                                         \
-        if (threadIdx.x == 0) plan_trace[i] = wall_clock64();    \
-    } while (0)
-#else
-#define ALLOCMOE_PLAN_STAMP(i)
-#endif
-
 template <bool SELECT, bool DISPATCH, int NT>
 __global__ __launch_bounds__(NT) void plan_fast_kernel(
     const float* topk_s, const int32_t* topk_ids, int T, int K, int Kb, int64_t B, int E,
@@ -392,7 +387,6 @@ __global__ __launch_bounds__(NT) void plan_fast_kernel(
     constexpr int NBINS_LOG2 = NT == 1024 ? 11 : 9;
     static_assert(NT == 1024 || NT == 256, "two block sizes");
     const int tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
-    ALLOCMOE_PLAN_STAMP(0);
 
     // Candidate ids of this wave's batches (lane = token), all loaded up front so that
     // the loads are in flight together, and kept in registers for both uses in the
@@ -491,7 +485,6 @@ __global__ __launch_bounds__(NT) void plan_fast_kernel(
                 }
             }
             if (staged) __syncthreads();   // the staging area is the dispatch arrays' from here on
-            ALLOCMOE_PLAN_STAMP(1);
             // ---- range of the keys
             uint32_t lo = 0xFFFFFFFFu, hi = 0u;
 #pragma unroll
@@ -520,7 +513,6 @@ __global__ __launch_bounds__(NT) void plan_fast_kernel(
                 lo = min(lo, sh.red_lo[w]);
                 hi = max(hi, sh.red_hi[w]);
             }
-            ALLOCMOE_PLAN_STAMP(2);
             // ---- narrowing passes (see select_phase)
             uint32_t r = static_cast<uint32_t>(want);
             uint32_t in_range = static_cast<uint32_t>(n_pool);
@@ -559,7 +551,6 @@ __global__ __launch_bounds__(NT) void plan_fast_kernel(
                 lo = new_lo;
                 __syncthreads();
             }
-            ALLOCMOE_PLAN_STAMP(3);
             const uint32_t vstar = lo, n_equal = in_range, R = r;
             // ---- equal keys that precede this thread's slice (only if a tie is split)
             uint32_t before = 0;
@@ -603,7 +594,6 @@ __global__ __launch_bounds__(NT) void plan_fast_kernel(
         __syncthreads();
     }
     if (!DISPATCH) return;
-    ALLOCMOE_PLAN_STAMP(4);
 
     const int n_batch = (T + kWave - 1) / kWave;
     if (NT != 256) load_held();
@@ -633,7 +623,6 @@ __global__ __launch_bounds__(NT) void plan_fast_kernel(
         sh.words[b * kWave + lane] = wave_transpose64(mine);
     }
     __syncthreads();
-    ALLOCMOE_PLAN_STAMP(5);
     // ---- B: per expert, exclusive prefix over batches; offsets over experts
     {
         const int e = tid % kWave, seg = tid / kWave;
@@ -660,12 +649,12 @@ __global__ __launch_bounds__(NT) void plan_fast_kernel(
             if (e == 0) sh.expert_off[0] = 0;
         }
         __syncthreads();
-        if (tid <= E) expert_offsets[tid] = sh.expert_off[tid];
+        if (tid <= E) expert_offsets[tid] = min(sh.expert_off[tid], static_cast<int32_t>(B));
     }
-    ALLOCMOE_PLAN_STAMP(6);
     // ---- tile map, by the last wave, beside the other waves' share of phase C (with few
     // tokens the last wave has no batch of its own)
-    if (tile_info != nullptr && wave == NW - 1) write_tile_map(sh.expert_off, E, bm, tile_info);
+    if (tile_info != nullptr && wave == NW - 1)
+        write_tile_map(sh.expert_off, E, bm, tile_info, static_cast<int>(B));
     // ---- C: place every pair
 #pragma unroll
     for (int bi = 0; bi < kMaxBatches; ++bi) {
@@ -694,21 +683,15 @@ __global__ __launch_bounds__(NT) void plan_fast_kernel(
                 if (row < B) {   // holds whenever sum_t keep_count[t] <= budget
                     row_token[row] = t;
                     row_rank[row] = j;
+                } else {
+                    row = -1;
                 }
             }
             inv_row[static_cast<size_t>(t) * K + j] = row;
         }
     }
-    ALLOCMOE_PLAN_STAMP(7);
-    ALLOCMOE_PLAN_STAMP(8);
-}
 
-#ifdef ALLOCMOE_TRACE
-extern "C" int allocmoe_debug_plan_trace(long long* host_out) {
-    return static_cast<int>(hipMemcpyFromSymbol(host_out, HIP_SYMBOL(plan_trace), sizeof(long long) * 16,
-                                                0, hipMemcpyDeviceToHost));
 }
-#endif
 
 // 0: large sizes (generic kernels), 256 / 1024: block size of the fast kernel.
 // Small problems run on 4 waves (one per SIMD): the kernel is a chain of short
@@ -734,7 +717,7 @@ __global__ __launch_bounds__(kPlanThreads) void dispatch_kernel(
     __shared__ PlanShared sh;
     dispatch_phase(sh, topk_ids, keep_count, T, K, E, B, expert_offsets, row_token, row_rank,
                    inv_row, words, prefix);
-    if (tile_info != nullptr) tilemap_phase(sh, E, bm, tile_info);
+    if (tile_info != nullptr) tilemap_phase(sh, E, bm, tile_info, static_cast<int>(B));
 }
 
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
@@ -747,7 +730,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
     __syncthreads();
     dispatch_phase(sh, topk_ids, keep_count, T, K, E, B, expert_offsets, row_token, row_rank,
                    inv_row, words, prefix);
-    if (tile_info != nullptr) tilemap_phase(sh, E, bm, tile_info);
+    if (tile_info != nullptr) tilemap_phase(sh, E, bm, tile_info, static_cast<int>(B));
 }
 
 // Keys of the calibrated baseline selectors (include/allocmoe.h, allocmoe_selector),

@@ -9,7 +9,7 @@ import torch
 from oracle import quant
 from paper_2604_08133_amd import binding as B, synth
 from paper_2604_08133_amd.layer import DeviceLayer
-from tests.test_gpu_layer import check_layer, sample_tokens
+from tests.test_gpu_layer import check_layer, sample_tokens, stratified_tokens
 
 pytestmark = pytest.mark.gpu
 
@@ -128,6 +128,19 @@ def test_deepseek_shapes_with_fp8_weights():
         ref2[k] = extra[k].float()
     check_layer(w2, layer2, dev=DeviceLayer(w2, layer2, weights_fp8=True), ref_layer=ref2,
                 tokens=sample_tokens(w2.T, 6, seed=10), tag="fp8 tile kernel")
+    # the prefill workload at full size (T = 4096, I = 1408: the contraction of the second
+    # GEMM is 22 steps of 64, which leaves the 8-bit loop's half pass): first and last row
+    # of every tile of the tile map
+    w3 = synth.deepseek_prefill()
+    extra = synth.make_layer(w3, only=("X", "bias"))
+    layer3, ref3 = dict(layer), dict(ref)
+    for k in ("X", "bias"):
+        layer3[k] = extra[k]
+        ref3[k] = extra[k].float()
+    check_layer(w3, layer3, dev=DeviceLayer(w3, layer3, weights_fp8=True), ref_layer=ref3,
+                tokens=lambda offs, rt: stratified_tokens(offs, rt, w3.T, per_tile="ends",
+                                                          dense_rows=1024),
+                tag="fp8 tile kernel, full size")
 
 
 def test_fp8_flag_is_checked():

@@ -19,9 +19,46 @@ def scaled_err(got, want):
     return float((got.double() - want.double()).abs().max() / want.double().abs().max().clamp_min(1e-30))
 
 
+def elementwise_rel_err(got, want, floor_frac=0.05):
+    """max |y - y_ref| / max(|y_ref|, floor), floor = floor_frac * max|y_ref|: the relative
+    error element by element, with an absolute floor because outputs cross zero.  Reported
+    next to the scaled error; the gate is the scaled error."""
+    want = want.double()
+    floor = floor_frac * want.abs().max().clamp_min(1e-30)
+    return float(((got.double() - want).abs() / want.abs().clamp_min(floor)).max())
+
+
+def stratified_tokens(expert_offsets, row_token, T, bm=256, dense_rows=256, per_tile="blocks"):
+    """Tokens chosen from the oracle's dispatch so that the rows behind them hit every tile
+    of the grouped GEMM's tile map (an expert's rows split evenly over ceil(rows / bm)
+    tiles), the first and the last row of every tile and, with per_tile="blocks", one row
+    of every 32-row block of every tile; plus the first and the last row of every
+    dense_rows-row tile of the shared expert (whose rows are the tokens themselves)."""
+    rows = set()
+    offs = expert_offsets.tolist()
+    for e in range(len(offs) - 1):
+        n_rows = offs[e + 1] - offs[e]
+        if n_rows == 0:
+            continue
+        n_tiles = (n_rows + bm - 1) // bm
+        rt = (n_rows + n_tiles - 1) // n_tiles
+        for i in range(n_tiles):
+            first = offs[e] + i * rt
+            cnt = min(rt, n_rows - i * rt)
+            rows.update((first, first + cnt - 1))
+            if per_tile == "blocks":
+                rows.update(first + b for b in range(0, cnt, 32))
+    toks = {int(row_token[r]) for r in rows}
+    for t0 in range(0, T, dense_rows):
+        toks.update((t0, min(T, t0 + dense_rows) - 1))
+    return sorted(toks)
+
+
 def check_layer(w, layer, budget=None, K_base=None, tokens=None, dev=None, tag="", ref_layer=None):
     """ref_layer: the tensors the oracle computes with where they differ from what the
-    device layer was built from (quantised weights: the values the codes stand for)."""
+    device layer was built from (quantised weights: the values the codes stand for).
+    tokens: None (all), a list, or a function (expert_offsets, row_token) -> list that
+    picks the checked tokens from the oracle's dispatch."""
     budget = w.budget if budget is None else budget
     K_base = w.K_base if K_base is None else K_base
     dev = dev or DeviceLayer(w, layer)
@@ -34,6 +71,12 @@ def check_layer(w, layer, budget=None, K_base=None, tokens=None, dev=None, tag="
 
     ref_scores = oracle.softmax(oracle.gate_logits(layer["X"], layer["Wg"], layer.get("bias")))
     assert torch.allclose(mid["scores"], ref_scores, atol=2e-6, rtol=1e-5), "scores"
+    if callable(tokens):
+        ids, s = oracle.topk(mid["scores"], w.K)
+        kept, _ = oracle.alloc_t(s, K_base, budget)
+        offs, row_token, _, _ = oracle.dispatch(ids, kept, w.E)
+        tokens = tokens(offs, row_token)
+        print(f"  outputs checked on {len(tokens)} tokens chosen from the dispatch", flush=True)
     ref = oracle.forward(layer, w.K, K_base, budget, scores=mid["scores"], tokens=tokens)
     for k in ("topk_ids", "topk_s", "keep_count", "expert_offsets", "row_token", "row_rank",
               "inv_row"):
@@ -43,7 +86,8 @@ def check_layer(w, layer, budget=None, K_base=None, tokens=None, dev=None, tag="
         assert torch.allclose(mid["shared_gate"].double(), ref["sgate"], atol=1e-5)
     got = Y if tokens is None else Y[list(tokens)]
     err = scaled_err(got, ref["Y"])
-    print(f"  scaled max err {err:.3e}", flush=True)
+    print(f"  scaled max err {err:.3e}; element-wise relative err (floor 5 % of max|y|) "
+          f"{elementwise_rel_err(got, ref['Y']):.3e}", flush=True)
     assert err <= TOL[w.dtype], err
     assert torch.isfinite(Y.float()).all()
     return dev
@@ -153,17 +197,21 @@ def sample_tokens(T, n, seed):
 
 
 def test_deepseek_prefill_full_size_sampled(deepseek_big):
-    # T = 4096, B = 12288 (0.5x), normal popularity bias; outputs checked on a
-    # seeded sample of tokens, indices on all of them.
+    # T = 4096, B = 12288 (0.5x), normal popularity bias; indices checked on all tokens,
+    # outputs on the tokens of stratified_tokens: every tile of the tile map, every 32-row
+    # block of every tile, each tile's first and last row, and the first and last row of
+    # every 256-row tile of the shared expert (a few hundred tokens).
     w8, layer8, _ = deepseek_big
     w = synth.deepseek_prefill()
     layer = dict(layer8)
     layer["X"] = layer8["X"][:w.T].contiguous()
     layer["bias"] = synth.make_layer(w, only=("bias",))["bias"]
     dev = DeviceLayer(w, layer)
-    toks = sample_tokens(w.T, 12, 1)
-    check_layer(w, layer, tokens=toks, dev=dev)
-    check_layer(w, layer, budget=24576, tokens=toks[:4], dev=dev, tag="(1.0x)")
+    pick = lambda offs, rt: stratified_tokens(offs, rt, w.T)
+    check_layer(w, layer, tokens=pick, dev=dev)
+    # full budget: first and last row of every tile
+    pick_ends = lambda offs, rt: stratified_tokens(offs, rt, w.T, per_tile="ends", dense_rows=w.T)
+    check_layer(w, layer, budget=24576, tokens=pick_ends, dev=dev, tag="(1.0x)")
     # 640 tokens of the same layer: both groups on the tile kernel with partly filled
     # tiles, the shared expert in tiles of fewer than 256 rows
     del dev
@@ -174,26 +222,30 @@ def test_deepseek_prefill_full_size_sampled(deepseek_big):
 
 
 def test_deepseek_stack_layer_full_size_sampled(deepseek_big):
-    # T = 8192 with Zipf popularity skew; a mid budget, the smallest (B = T) and
-    # a ragged one
+    # T = 8192 with Zipf popularity skew; a mid budget (outputs on stratified_tokens: every
+    # tile, every 32-row block of every tile, first and last rows, the shared expert's row
+    # tiles), the smallest budget (B = T) and a ragged one (first and last row of every tile)
     w, layer, dev = deepseek_big
-    toks = sample_tokens(w.T, 8, 2)
-    check_layer(w, layer, budget=24576, tokens=toks, dev=dev)
-    check_layer(w, layer, budget=8192, tokens=toks[:3], dev=dev, tag="(B=T)")
-    check_layer(w, layer, budget=31337, tokens=toks[:3], dev=dev, tag="(ragged)")
+    check_layer(w, layer, budget=24576, tokens=lambda offs, rt: stratified_tokens(offs, rt, w.T),
+                dev=dev)
+    pick_ends = lambda offs, rt: stratified_tokens(offs, rt, w.T, per_tile="ends", dense_rows=w.T)
+    check_layer(w, layer, budget=8192, tokens=pick_ends, dev=dev, tag="(B=T)")
+    check_layer(w, layer, budget=31337, tokens=pick_ends, dev=dev, tag="(ragged)")
 
 
 def test_qwen_full_size_sampled():
     # the Qwen1.5-MoE-A2.7B-shaped layer at the size bench.py times: T = 2048, 60 experts, Top-4, gated shared
-    # expert of width 5632; the swept budgets 0.5x / 0.75x / 1.0x; outputs on a seeded
-    # sample of tokens, indices on all of them.  Weights made on the CPU once.
+    # expert of width 5632; the swept budgets 0.5x / 0.75x / 1.0x; indices on all tokens,
+    # outputs on stratified_tokens (0.5x: every tile, every 32-row block, first and last
+    # rows, the shared expert's row tiles; the other budgets: first and last row of every
+    # tile).  Weights made on the CPU once.
     w = synth.qwen_moe()
     layer = synth.make_layer(w)
     dev = DeviceLayer(w, layer)
-    toks = sample_tokens(w.T, 8, 3)
-    check_layer(w, layer, tokens=toks, dev=dev)                                  # 0.5x
-    check_layer(w, layer, budget=6144, tokens=toks[:3], dev=dev, tag="(0.75x)")
-    check_layer(w, layer, budget=8192, tokens=toks[:3], dev=dev, tag="(1.0x)")
+    check_layer(w, layer, tokens=lambda offs, rt: stratified_tokens(offs, rt, w.T), dev=dev)   # 0.5x
+    pick_ends = lambda offs, rt: stratified_tokens(offs, rt, w.T, per_tile="ends", dense_rows=w.T)
+    check_layer(w, layer, budget=6144, tokens=pick_ends, dev=dev, tag="(0.75x)")
+    check_layer(w, layer, budget=8192, tokens=pick_ends, dev=dev, tag="(1.0x)")
 
 
 def test_forward_is_bitwise_reproducible():

@@ -151,3 +151,34 @@ def test_seeded_random_cases():
             s = torch.full((T, E), 0.125)
         print(f"random case {n}: T={T} E={E} K={K} Kb={Kb} B={budget} {kind}", flush=True)
         assert_same(gpu_route_dispatch(s, K, Kb, budget), oracle_route_dispatch(s, K, Kb, budget), n)
+
+
+@pytest.mark.parametrize("T", [500, 9000])   # the single-workgroup kernel, the large-size kernels
+def test_dispatch_with_keep_counts_above_the_budget_stays_inside_it(T):
+    # the caller's keep counts sum to more than desc->budget (a contract violation the host
+    # cannot see): nothing may leave the kernel that points past the budget's rows
+    E, K = 16, 4
+    scores = synth.make_scores(T, E, seed=77)
+    ids, _ = oracle.topk(scores, K)
+    budget = T * 2
+    desc = B.make_desc(T, 64, E, 64, K, 1, budget, "f32")
+    cnt = torch.full((T,), 3, dtype=torch.int32, device=DEV)          # sums to 3T > 2T
+    offs = torch.empty((E + 1,), dtype=torch.int32, device=DEV)
+    guard = 64
+    row_token = torch.full((budget + guard,), -7, dtype=torch.int32, device=DEV)
+    row_rank = torch.full((budget + guard,), -7, dtype=torch.int32, device=DEV)
+    inv_row = torch.empty((T, K), dtype=torch.int32, device=DEV)
+    ws = torch.empty(B.allocmoe_workspace_layout(desc).scores, dtype=torch.uint8, device=DEV)
+    B.allocmoe_dispatch(desc, ids.to(DEV), cnt, offs, row_token, row_rank, inv_row, ws)
+    torch.cuda.synchronize()
+    assert int(inv_row.max()) < budget and int(inv_row.min()) >= -1
+    assert int(offs.max()) <= budget and int(offs[0]) == 0
+    assert bool((offs[1:] >= offs[:-1]).all())
+    assert bool((row_token[budget:] == -7).all()) and bool((row_rank[budget:] == -7).all())
+    placed = inv_row[inv_row >= 0]
+    assert placed.numel() == budget and placed.unique().numel() == budget   # every row used once
+    # rows that exist are consistent with the pair behind them
+    r = inv_row.cpu()
+    tt, jj = torch.nonzero(r >= 0, as_tuple=True)
+    assert torch.equal(row_token.cpu()[r[tt, jj].long()], tt.int())
+    assert torch.equal(row_rank.cpu()[r[tt, jj].long()], jj.int())
