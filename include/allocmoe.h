@@ -337,6 +337,23 @@ typedef enum allocmoe_schedule {
 allocmoe_status allocmoe_layer_schedule(allocmoe_schedule kind, int32_t L, int32_t K_orig,
                                         int64_t B, int32_t *K_out);
 
+/* allocmoe_dispatch for callers that cannot allocate device memory or pass a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc):
+ * the same kernels and the same outputs, but the scratch (ballot words and prefixes,
+ * 768 bytes per 64 tokens) lives in a buffer of ALLOCMOE_STATIC_SCRATCH_BYTES that is
+ * part of the library's device image (every GPU the library runs on holds its own copy
+ * until the process ends).  Sizes beyond ALLOCMOE_STATIC_MAX_TOKENS tokens are rejected
+ * with ALLOCMOE_ESHAPE.  Allocates nothing, frees nothing and calls no allocating
+ * routine.  Every call on a GPU shares that GPU's buffer (nothing in it has to start at
+ * zero: each call writes what it reads), so calls that overlap in time on one GPU (two
+ * streams, two threads) race; calls on one stream are ordered and safe. */
+#define ALLOCMOE_STATIC_MAX_TOKENS 65536
+#define ALLOCMOE_STATIC_SCRATCH_BYTES (ALLOCMOE_STATIC_MAX_TOKENS / 64 * 768)
+allocmoe_status allocmoe_dispatch_static(const allocmoe_layer_desc *desc, const int32_t *topk_ids,
+                                         const int32_t *keep_count, int32_t *expert_offsets,
+                                         int32_t *row_token, int32_t *row_rank, int32_t *inv_row,
+                                         allocmoe_stream stream);
+
 const char *allocmoe_status_string(allocmoe_status status);
 
 #ifdef __cplusplus

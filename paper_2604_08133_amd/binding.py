@@ -21,7 +21,7 @@ F32, BF16 = 0, 1
 EXPORTS = [
     "allocmoe_workspace_bytes", "allocmoe_workspace_layout", "allocmoe_packed_bytes",
     "allocmoe_pack_weights", "allocmoe_route", "allocmoe_route_from_scores",
-    "allocmoe_dispatch", "allocmoe_moe_forward", "allocmoe_moe_forward_timed",
+    "allocmoe_dispatch", "allocmoe_dispatch_static", "allocmoe_moe_forward", "allocmoe_moe_forward_timed",
     "allocmoe_alloc_l", "allocmoe_layer_schedule", "allocmoe_routing_stats",
     "allocmoe_probe_mfma_operand_bytes", "allocmoe_probe_sink_bytes", "allocmoe_probe_mfma",
     "allocmoe_probe_hbm_read",
@@ -181,6 +181,18 @@ def allocmoe_dispatch(desc: LayerDesc, topk_ids, keep_count, expert_offsets, row
                                     _ptr(inv_row), _ptr(ws),
                                     ctypes.c_size_t(ws.numel() * ws.element_size()),
                                     _stream(stream)), "allocmoe_dispatch")
+
+
+STATIC_MAX_TOKENS = 65536
+
+
+def allocmoe_dispatch_static(desc: LayerDesc, topk_ids, keep_count, expert_offsets, row_token,
+                             row_rank, inv_row, stream=None) -> None:
+    """allocmoe_dispatch with the library's own static scratch: no workspace argument."""
+    _check(load().allocmoe_dispatch_static(ctypes.byref(desc), _ptr(topk_ids), _ptr(keep_count),
+                                           _ptr(expert_offsets), _ptr(row_token), _ptr(row_rank),
+                                           _ptr(inv_row), _stream(stream)),
+           "allocmoe_dispatch_static")
 
 
 def allocmoe_moe_forward(desc: LayerDesc, X, w: Weights, Y, ws: torch.Tensor, stream=None) -> None:

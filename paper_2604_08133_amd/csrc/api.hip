@@ -367,8 +367,13 @@ struct DeviceState {
     hipEvent_t fork = nullptr, join = nullptr;
     hipEvent_t ev[kTimedEvents] = {};
     bool have_ev = false;
+    unsigned char* static_scratch = nullptr;   // this device's copy of `scratch` (below)
 };
 
+// Scratch of allocmoe_dispatch_static.  In host code this name is only a handle for
+// hipGetSymbolAddress: every device holds its own copy at its own address, kept in
+// DeviceState::static_scratch.
+static __device__ __align__(256) unsigned char scratch[ALLOCMOE_STATIC_SCRATCH_BYTES];
 
 allocmoe_status device_state_of_current_device(DeviceState** out) {
     constexpr int kMaxDevices = 64;
@@ -629,6 +634,39 @@ allocmoe_status forward_impl(const allocmoe_layer_desc* desc, const void* X,
 }  // namespace
 
 extern "C" {
+
+allocmoe_status allocmoe_dispatch_static(const allocmoe_layer_desc* desc, const int32_t* topk_ids,
+                                         const int32_t* keep_count, int32_t* expert_offsets,
+                                         int32_t* row_token, int32_t* row_rank, int32_t* inv_row,
+                                         allocmoe_stream stream_) {
+    const allocmoe_status st = check_desc(desc);
+    if (st != ALLOCMOE_OK) return st;
+    if (!topk_ids || !keep_count || !expert_offsets || !inv_row) return ALLOCMOE_EINVAL;
+    if (desc->budget > 0 && (!row_token || !row_rank)) return ALLOCMOE_EINVAL;
+    if (desc->T > ALLOCMOE_STATIC_MAX_TOKENS) return ALLOCMOE_ESHAPE;
+    const Scratch s = scratch_of(desc);
+    if (s.tile_info > ALLOCMOE_STATIC_SCRATCH_BYTES) return ALLOCMOE_ESHAPE;   // words + prefixes
+    DeviceState* state = nullptr;
+    const allocmoe_status dst = device_state_of_current_device(&state);
+    if (dst != ALLOCMOE_OK) return dst;
+    unsigned char* base = nullptr;
+    {
+        std::lock_guard<std::mutex> guard(state->lock);
+        if (state->static_scratch == nullptr) {   // once per device, with that device current
+            void* p = nullptr;
+            ALLOCMOE_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+            if (p == nullptr) return ALLOCMOE_EHIP;
+            state->static_scratch = static_cast<unsigned char*>(p);
+        }
+        base = state->static_scratch;
+    }
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    ALLOCMOE_TRY(launch_dispatch(topk_ids, keep_count, desc->T, desc->K, desc->E, desc->budget,
+                                 expert_offsets, row_token, row_rank, inv_row,
+                                 at<uint64_t>(base, s.words), at<int32_t>(base, s.prefix),
+                                 kTileRowsSmall, nullptr, stream));
+    return ALLOCMOE_OK;
+}
 
 allocmoe_status allocmoe_moe_forward(const allocmoe_layer_desc* desc, const void* X,
                                      const allocmoe_weights* w, void* Y, void* ws,
