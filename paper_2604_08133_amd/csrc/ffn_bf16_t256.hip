@@ -49,7 +49,9 @@ constexpr int kSlots = 4;
 constexpr int kWaves = 4;
 constexpr int kSlotBytes = kRows * kStepK * 2;
 constexpr int kXcds = 8;                // accelerator dies (one L2 each) of an MI355X
-constexpr int kBRing = 8;               // k16 steps of weight fragments held in registers
+constexpr int kBRing = 8;               // 16-byte units of weight fragments held per stream (k16 steps with bf16)
+constexpr int kBRingDeep = 24;          // the same for tiles of at most kLightRowBlocks row blocks
+constexpr int kLightRowBlocks = 2;
 
 
 // 8 rows x 128 B of activations, global -> LDS directly: lane l's 16 bytes land
@@ -99,7 +101,7 @@ __device__ __forceinline__ bf16x8 widen_fp8x8(uint2 q) {
 // b0, b1: the wave's two weight streams (bf16 fragments, or with FP8 the codes: a lane's
 // 16 bytes per 32 k hold its fragment of the even k16 step, then of the odd one);
 // sc0, sc1: with FP8 the scales of the 32 columns of each stream.
-template <bool SWIGLU, int NRB, bool STREAM_ONCE, bool FP8>
+template <bool SWIGLU, int NRB, bool STREAM_ONCE, bool FP8, int RING>
 __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda,
                                           const int32_t* row_map, const void* b0,
                                           const void* b1, const float* sc0, const float* sc1,
@@ -132,7 +134,7 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
             load_rows_to_lds(arow[i] + s * (kStepK / 8), lds_wave + slot * kSlotBytes + i * 4096);
     };
     typedef __attribute__((__vector_size__(4 * sizeof(int)))) int i32x4;
-    i32x4 breg[kBRing][2];
+    i32x4 breg[RING][2];
     // Weight fragments come through buffer loads: a scalar descriptor per stream
     // (base, size), the lane's offset in a VGPR and the k16 step's offset in an SGPR,
     // so a load costs no address arithmetic on the vector unit; a step past the end
@@ -222,16 +224,22 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
     // ring entry both steps used, refilled for 16 steps later); between the loads of
     // slot s+1 and the wait for it: 2 + (2 + NRB + 2) + 2.  The prologue keeps that
     // count by placing the surplus weight loads before slot 1.
-    constexpr int kPass = FP8 ? 16 : 8;
+    // A deeper ring (RING k16 steps, bf16 only) changes nothing in these counts: the loads
+    // of slot j sit right before the weight loads of step 4 j - 9 + RING in the steady
+    // state, and so they do in the prologue.  At most 63 loads can be outstanding per wave
+    // (2 RING + 3 NRB here), which bounds RING for the row-block counts that use it.
+    static_assert(!FP8 || RING == 8, "8-bit weights: ring of 8 units = 16 steps");
+    static_assert(2 * RING + 3 * NRB <= 63, "outstanding loads per wave");
+    constexpr int kPass = FP8 ? 16 : RING;
     constexpr int kWaitA = FP8 ? 8 + NRB : 16 + NRB;
     issue_a(0, 0);
 #pragma unroll
-    for (int r = 0; r < kBRing; ++r) {
+    for (int r = 0; r < RING; ++r) {
         load_b(r, r);
-        if (r == (FP8 ? 4 : 2)) issue_a(min(1, KT - 1), 1);
-        if (r == 6) issue_a(min(2, KT - 1), 2);
+        if (r == (FP8 ? 4 : RING - 6)) issue_a(min(1, KT - 1), 1);
+        if (r == RING - 2) issue_a(min(2, KT - 1), 2);
     }
-    wait_vmcnt_le<2 * kBRing + 2 * NRB>();   // slot 0 has landed (this wave's part)
+    wait_vmcnt_le<2 * RING + 2 * NRB>();   // slot 0 has landed (this wave's part)
     wg_barrier_nofence();
     bf16x8 af[2][NRB];
     read_a(0, 0, af[0]);
@@ -267,9 +275,9 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
             }
             __builtin_amdgcn_sched_barrier(0);
             if constexpr (!FP8)
-                load_b(4 * s2 + u + kBRing, u);
+                load_b(4 * s2 + u + RING, u);
             else if (u & 1)
-                load_b(2 * s2 + u / 2 + kBRing, u / 2);
+                load_b(2 * s2 + u / 2 + RING, u / 2);
             if (kc == 2) {
                 // this wave's part of the next slot has landed; after the barrier
                 // everybody's has, and everybody is done with the slot before this one
@@ -280,8 +288,14 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
     };
     int s2 = 0;
     for (; s2 + kPass / 4 <= KT; s2 += kPass / 4) pass(s2, std::integral_constant<int, kPass>{});
-    // (KT is even; with 16-step passes a half pass may remain)
-    if (kPass == 16 && s2 < KT) pass(s2, std::integral_constant<int, 8>{});
+    // (KT is even, so what remains of the contraction is a multiple of 8 steps below kPass)
+    if constexpr (kPass >= 16) {
+        if (KT - s2 == 2) pass(s2, std::integral_constant<int, 8>{});
+    }
+    if constexpr (kPass >= 24) {
+        if (KT - s2 == 4) pass(s2, std::integral_constant<int, 16>{});
+    }
+    static_assert(kPass == 8 || kPass == 16 || kPass == 24, "remainder passes");
     __builtin_amdgcn_sched_barrier(0);
     wait_vmcnt_le<0>();   // the surplus loads have landed before registers and LDS are reused
 
@@ -371,14 +385,31 @@ __global__ __launch_bounds__(kWaves* kWave, 1) void ffn_bf16_t256_kernel(StreamG
         if (g0.A == nullptr) return;
         int sub = idx - S;
         if (g0.tile_info != nullptr) {
-            const int tiles = g0.tile_info[0];
+            const int tiles = g0.tile_info[0], light = g0.tile_info[1], heavy = tiles - light;
             // (pairs dealt in serpentine order: even rounds left to right, odd rounds
             // right to left, which evens out the XCDs' totals of the sorted tile costs)
             const int round = sub / (2 * nt0), in_pair = sub % (2 * nt0);
-            const int pair = round * kXcds + ((round & 1) ? kXcds - 1 - xcd : xcd);
-            tile = 2 * pair + in_pair % 2;
+            const int q = round * kXcds + ((round & 1) ? kXcds - 1 - xcd : xcd);
+            // The light tiles (single tiles of at most kLightRowBlocks row blocks: the end
+            // of the tile map) wait for their weights, the others for the matrix unit:
+            // their pairs are spread evenly among the pairs of the others, so that both
+            // kinds run side by side through the whole launch.  Of the first q + 1 pair
+            // positions floor((q + 1) n_light / n_pairs) hold light pairs.
+            const int hp = (heavy + 1) / 2, lp = (light + 1) / 2, np = hp + lp;
+            if (q >= np) return;   // the grid is sized for the host's bound
+            const int lq = static_cast<int>(static_cast<int64_t>(q + 1) * lp / np);
+            const int lq0 = static_cast<int>(static_cast<int64_t>(q) * lp / np);
+            int first_of_pair, end;
+            if (lq > lq0) {
+                first_of_pair = heavy + 2 * lq0;
+                end = tiles;
+            } else {
+                first_of_pair = 2 * (q - lq0);
+                end = heavy;
+            }
+            tile = first_of_pair + in_pair % 2;
             nt = in_pair / 2;
-            if (tile >= tiles) return;   // the grid is sized for the host's bound
+            if (tile >= end) return;
         } else {   // a dense group in the first slot: its row tiles striped over the XCDs
             const int tiles = (g0.M_dense + g0.dense_rows - 1) / g0.dense_rows;
             tile = sub / nt0 * kXcds + xcd;
@@ -433,14 +464,16 @@ __global__ __launch_bounds__(kWaves* kWave, 1) void ffn_bf16_t256_kernel(StreamG
     }
 
 #define ALLOCMOE_T256_CASE(n)                                                                       \
-    case n:                                                                                         \
+    case n: {                                                                                       \
+        constexpr int kRing = (!FP8 && n <= kLightRowBlocks) ? kBRingDeep : kBRing;                 \
         if (only_tile)                                                                              \
-            t256_body<SWIGLU, n, true, FP8>(lds, A, lda, row_map, b0, b1, sc0, sc1, KT, wave, lane, \
-                                            row0, rows, nt, g.C, ldc);                              \
+            t256_body<SWIGLU, n, true, FP8, kRing>(lds, A, lda, row_map, b0, b1, sc0, sc1, KT,      \
+                                                   wave, lane, row0, rows, nt, g.C, ldc);           \
         else                                                                                        \
-            t256_body<SWIGLU, n, false, FP8>(lds, A, lda, row_map, b0, b1, sc0, sc1, KT, wave,      \
-                                             lane, row0, rows, nt, g.C, ldc);                       \
-        break;
+            t256_body<SWIGLU, n, false, FP8, kRing>(lds, A, lda, row_map, b0, b1, sc0, sc1, KT,     \
+                                                    wave, lane, row0, rows, nt, g.C, ldc);          \
+        break;                                                                                      \
+    }
     switch (n_rb) {   // uniform over the workgroup
         ALLOCMOE_T256_CASE(1)
         ALLOCMOE_T256_CASE(2)
@@ -483,7 +516,8 @@ hipError_t launch_ffn_bf16_t256(bool swiglu, StreamGroup routed, StreamGroup sha
     if (routed.A != nullptr) {
         int64_t tiles;   // per XCD
         if (routed.tile_info != nullptr)
-            tiles = 2 * (((routed.max_tiles + 1) / 2 + kXcds - 1) / kXcds);   // whole pairs
+            // whole pairs; light and other tiles pair among themselves: one pair more
+            tiles = 2 * (((routed.max_tiles + 1) / 2 + 1 + kXcds - 1) / kXcds);
         else
             tiles = ((routed.M_dense + routed.dense_rows - 1) / routed.dense_rows + kXcds - 1) / kXcds;
         per_xcd += tiles * (routed.N / cols);

@@ -11,8 +11,9 @@ namespace allocmoe {
 // rows per tile of the grouped-GEMM tile map written by the plan kernel
 constexpr int kTileRowsSmall = 32;
 
-// tile_info layout: [0] = number of tiles; entry i at [kTileHdr + 4*i]: expert,
-// first row, rows in tile, number of tiles of this expert.
+// tile_info layout: [0] = number of tiles; [1] = how many of them, at the end of the
+// list, are the only tile of an expert with at most 64 rows; entry i at
+// [kTileHdr + 4*i]: expert, first row, rows in tile, number of tiles of this expert.
 //
 // An expert's rows are split evenly over its ceil(rows / bm) tiles, so the tiles
 // of one expert cost the same.  Experts are listed by decreasing rows per tile

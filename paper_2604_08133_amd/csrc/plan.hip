@@ -304,6 +304,9 @@ __device__ __forceinline__ void write_tile_map(const int32_t* expert_off, int E,
         ent[3] = n;
     }
     if (lane == kWave - 1) tile_info[0] = incl;
+    // [1]: the single tiles of at most 64 rows (they end the list: fewest rows per tile)
+    const uint64_t light = __ballot(n == 1 && rt <= 64);
+    if (lane == 0) tile_info[1] = __popcll(light);
 }
 
 __device__ void tilemap_phase(PlanShared& sh, int E, int bm, int32_t* __restrict__ tile_info,
