@@ -151,8 +151,11 @@ typedef struct {
  * descriptor.  The workspace is device memory, 256-byte aligned, contents
  * undefined on entry, reusable across calls on the same stream.
  * allocmoe_dispatch uses only its first allocmoe_ws_layout.scores bytes (the
- * scratch region, which starts the workspace); allocmoe_route and
- * allocmoe_route_from_scores use none (ws may be NULL). */
+ * scratch region, which starts the workspace).  allocmoe_route and
+ * allocmoe_route_from_scores need none (ws may be NULL: one workgroup then does the
+ * selection, whatever T); given a workspace of at least allocmoe_ws_layout.scores
+ * bytes they spread the selection over many workgroups from 4096 tokens on (same
+ * result, bit for bit). */
 allocmoe_status allocmoe_workspace_bytes(const allocmoe_layer_desc *desc, size_t *bytes);
 allocmoe_status allocmoe_workspace_layout(const allocmoe_layer_desc *desc,
                                           allocmoe_ws_layout *layout);

@@ -17,7 +17,7 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 inline size_t elem_size(int dtype) { return dtype == ALLOCMOE_F32 ? 4u : 2u; }
 
 struct Scratch {       // offsets inside the scratch region (which starts the workspace)
-    size_t words, prefix, tile_info, bytes;
+    size_t words, prefix, tile_info, spread, bytes;
     int64_t max_tiles;
 };
 
@@ -39,6 +39,8 @@ Scratch scratch_of(const allocmoe_layer_desc* d) {
     s.tile_info = off;
     s.max_tiles = max_tiles_for(d, kTileRowsSmall);
     off = align_up(off + tile_info_ints(s.max_tiles) * sizeof(int32_t));
+    s.spread = off;   // partial histograms of the many-workgroup selection
+    off = align_up(off + plan_spread_bytes(d->T));
     s.bytes = off;
     return s;
 }
@@ -261,11 +263,16 @@ allocmoe_status allocmoe_route(const allocmoe_layer_desc* desc, const void* X,
     const allocmoe_status st = check_desc(desc);
     if (st != ALLOCMOE_OK) return st;
     if (!X || !w || !w->Wg || !topk_ids || !topk_s || !keep_count) return ALLOCMOE_EINVAL;
-    // the selection runs out of LDS; only the selector keys need device scratch
+    // one workgroup selects out of LDS; the selector keys need device scratch, and so does
+    // the many-workgroup selection (used when the workspace has room for it)
     const bool keyed = selector_of(desc) != ALLOCMOE_SELECT_SCORE;
-    const size_t key_bytes = static_cast<size_t>(desc->T) * desc->K * 4;
+    const size_t key_bytes = keyed ? align_up(static_cast<size_t>(desc->T) * desc->K * 4) : 0;
     if (keyed && (ws == nullptr || ws_bytes < key_bytes || !aligned(ws, kAlign)))
         return ALLOCMOE_EWORKSPACE;
+    void* spread = nullptr;
+    if (ws != nullptr && aligned(ws, kAlign) && plan_spread_bytes(desc->T) > 0 &&
+        ws_bytes >= key_bytes + plan_spread_bytes(desc->T))
+        spread = static_cast<char*>(ws) + key_bytes;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     if (desc->dtype == ALLOCMOE_BF16 && w->packed != nullptr) {
         if (!aligned(w->packed, kAlign) || !aligned(X, 16)) return ALLOCMOE_EINVAL;
@@ -283,7 +290,7 @@ allocmoe_status allocmoe_route(const allocmoe_layer_desc* desc, const void* X,
         keys = static_cast<const float*>(ws);
     }
     ALLOCMOE_TRY(launch_select(keys, desc->T, desc->K, desc->K_base, desc->budget, keep_count,
-                               stream));
+                               spread, stream));
     return ALLOCMOE_OK;
 }
 
@@ -295,9 +302,13 @@ allocmoe_status allocmoe_route_from_scores(const allocmoe_layer_desc* desc, cons
     if (st != ALLOCMOE_OK) return st;
     if (!scores || !topk_ids || !topk_s || !keep_count) return ALLOCMOE_EINVAL;
     const bool keyed = selector_of(desc) != ALLOCMOE_SELECT_SCORE;
-    const size_t key_bytes = static_cast<size_t>(desc->T) * desc->K * 4;
+    const size_t key_bytes = keyed ? align_up(static_cast<size_t>(desc->T) * desc->K * 4) : 0;
     if (keyed && (ws == nullptr || ws_bytes < key_bytes || !aligned(ws, kAlign)))
         return ALLOCMOE_EWORKSPACE;
+    void* spread = nullptr;
+    if (ws != nullptr && aligned(ws, kAlign) && plan_spread_bytes(desc->T) > 0 &&
+        ws_bytes >= key_bytes + plan_spread_bytes(desc->T))
+        spread = static_cast<char*>(ws) + key_bytes;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     ALLOCMOE_TRY(launch_topk_from_scores(scores, desc->T, desc->E, desc->K, topk_ids, topk_s, stream));
     const float* keys = topk_s;
@@ -307,7 +318,7 @@ allocmoe_status allocmoe_route_from_scores(const allocmoe_layer_desc* desc, cons
         keys = static_cast<const float*>(ws);
     }
     ALLOCMOE_TRY(launch_select(keys, desc->T, desc->K, desc->K_base, desc->budget, keep_count,
-                               stream));
+                               spread, stream));
     return ALLOCMOE_OK;
 }
 
@@ -540,7 +551,12 @@ allocmoe_status forward_impl(const allocmoe_layer_desc* desc, const void* X,
         ALLOCMOE_TRY(hipEventRecord(side->fork, stream));
         ALLOCMOE_TRY(hipStreamWaitEvent(side->stream, side->fork, 0));
     }
-    // steps 3-4: Alloc-T selection, dispatch, tile map
+    // steps 3-4: Alloc-T selection, dispatch, tile map.  Beside the shared expert's GEMMs
+    // (which hide it, and whose workgroups hold every compute unit for tens of
+    // microseconds at a time) one workgroup does it in one launch, enqueued before them;
+    // otherwise, from kPlanSpreadTokens tokens on, a sequence of short launches over many
+    // workgroups.
+    const bool spread_plan = plan_spread_bytes(T) > 0 && !overlap;
     ALLOCMOE_MARK(ALLOCMOE_STAGE_PLAN);
     const float* sel_keys = topk_s;   // Alloc-T selects on the scores themselves
     if (selector_of(desc) != ALLOCMOE_SELECT_SCORE) {
@@ -551,7 +567,7 @@ allocmoe_status forward_impl(const allocmoe_layer_desc* desc, const void* X,
     ALLOCMOE_TRY(launch_plan(sel_keys, topk_ids, T, K, desc->K_base, B, E, keep_count,
                              expert_offsets, row_token, row_rank, inv_row,
                              at<uint64_t>(scr, s.words), at<int32_t>(scr, s.prefix), bm, tile_info,
-                             stream));
+                             spread_plan ? scr + s.spread : nullptr, stream));
     if (overlap && shared_tiled) {
         for (int half = 0; half < 2; ++half) {
             ALLOCMOE_MARK_ON(half == 0 ? kEvSide0 : kEvSide1, side->stream);

@@ -44,8 +44,16 @@ hipError_t launch_topk_from_scores(const float* scores, int T, int E, int K, int
 // candidate scores [T,K]
 hipError_t launch_selector_keys(const float* topk_s, int T, int K, int mode, float* keys,
                                 hipStream_t stream);
+// From kPlanSpreadTokens tokens on, selection and dispatch run as a sequence of launches
+// over many workgroups; the selection then needs plan_spread_bytes(T) bytes of device
+// scratch (`spread`, 256-byte aligned; null: one workgroup does the work, whatever T).
+// Every launch of the sequence costs 5-10 us whatever its size (a chain of dependent
+// memory round trips), five of them 42 us at 8192 tokens and 36 us at 4096, against 82 us
+// and 50 us for the single workgroup; at 2048 tokens both take 32 us.
+constexpr int kPlanSpreadTokens = 4096;
+size_t plan_spread_bytes(int T);
 hipError_t launch_select(const float* topk_s, int T, int K, int Kb, int64_t B,
-                         int32_t* keep_count, hipStream_t stream);
+                         int32_t* keep_count, void* spread, hipStream_t stream);
 hipError_t launch_dispatch(const int32_t* topk_ids, const int32_t* keep_count, int T, int K,
                            int E, int64_t B, int32_t* expert_offsets, int32_t* row_token,
                            int32_t* row_rank, int32_t* inv_row, uint64_t* words, int32_t* prefix,
@@ -53,7 +61,8 @@ hipError_t launch_dispatch(const int32_t* topk_ids, const int32_t* keep_count, i
 hipError_t launch_plan(const float* topk_s, const int32_t* topk_ids, int T, int K, int Kb,
                        int64_t B, int E, int32_t* keep_count, int32_t* expert_offsets,
                        int32_t* row_token, int32_t* row_rank, int32_t* inv_row, uint64_t* words,
-                       int32_t* prefix, int bm, int32_t* tile_info, hipStream_t stream);
+                       int32_t* prefix, int bm, int32_t* tile_info, void* spread,
+                       hipStream_t stream);
 
 // ---- ffn_f32.hip : C = A B (or silu(A B1) * (A B3)) over row tiles, fp32, row-major B
 // A rows are taken through row_map when it is not null.  With tile_info null the

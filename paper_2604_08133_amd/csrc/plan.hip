@@ -696,6 +696,277 @@ __global__ __launch_bounds__(NT) void plan_fast_kernel(
 
 }
 
+// ---------------------------------------------------------------------------
+// Many tokens (T >= kPlanSpreadTokens): the same selection and dispatch spread over
+// workgroups, as a fixed sequence of short launches, with no global atomics and no
+// waiting between workgroups (what a later launch needs from all workgroups of an
+// earlier one goes through memory).
+//
+// Selection: exact radix select of the B'-th largest pool key on the 32 key bits, 11 +
+// 11 + 10 from the top.  Pass p: each of G workgroups histograms, in LDS, the digit p of
+// its share of the pool keys whose higher digits equal the ones already found, and writes
+// its 2048 counts to hist[p][g]; the next launch sums the G partial histograms per bin,
+// walks them from the top and finds the digit that holds the wanted rank (every workgroup
+// does this redundantly, workgroup 0 records digit and remaining rank for the launches
+// after it).  After three passes the key v* and the number R of keys equal to v* that
+// are kept are known.  keep: thread = token; ties at v* are split in (token, rank) order:
+// a workgroup counts the equal keys of all earlier tokens itself (only when a tie is
+// split).  The same launch forms the ballot words of its batches of 64 tokens.
+// place: a workgroup owns 16 batches; per expert (lane) the counts of all batches and of
+// the batches before its own come from popcounts of the ballot words; then the rows.
+constexpr int kSpreadThreads = 1024;   // (kPlanSpreadTokens: kernels.hpp)
+constexpr int kSpreadMaxGroups = 16;
+constexpr int kSpreadBins = 2048;
+
+struct SpreadState {
+    uint32_t b1, r1, b2, r2;
+};
+
+inline int spread_groups(int T) {
+    const int g = (T + kSpreadThreads - 1) / kSpreadThreads;
+    return g < kSpreadMaxGroups ? g : kSpreadMaxGroups;
+}
+
+size_t plan_spread_bytes(int T) {
+    if (T < kPlanSpreadTokens) return 0;
+    return 3 * static_cast<size_t>(spread_groups(T)) * kSpreadBins * sizeof(uint32_t) + 256;
+}
+
+// The bin (of the G partial histograms summed) that holds the r-th largest key counted
+// from the top bin, the rank inside it and its count.  Block-wide; every thread returns
+// the same values.
+__device__ __forceinline__ void spread_find_bin(const uint32_t* __restrict__ partials, int G,
+                                                uint32_t r, uint32_t* wave_tot, uint32_t* pick,
+                                                uint32_t& bin, uint32_t& rank, uint32_t& count) {
+    const int tid = threadIdx.x;
+    const int b_first = kSpreadBins - 1 - 2 * tid, b_second = b_first - 1;
+    uint32_t c_first = 0, c_second = 0;
+    for (int g = 0; g < G; ++g) {
+        c_first += partials[static_cast<size_t>(g) * kSpreadBins + b_first];
+        c_second += partials[static_cast<size_t>(g) * kSpreadBins + b_second];
+    }
+    const uint32_t above = block_scan_excl(c_first + c_second, wave_tot, nullptr);
+    if (above < r && r <= above + c_first) {
+        pick[0] = b_first;
+        pick[1] = r - above;
+        pick[2] = c_first;
+    } else if (above + c_first < r && r <= above + c_first + c_second) {
+        pick[0] = b_second;
+        pick[1] = r - above - c_first;
+        pick[2] = c_second;
+    }
+    __syncthreads();
+    bin = pick[0];
+    rank = pick[1];
+    count = pick[2];
+    __syncthreads();
+}
+
+template <int PASS>
+__global__ __launch_bounds__(kSpreadThreads) void spread_hist_kernel(
+    const float* __restrict__ keys, int T, int K, int Kb, int64_t B, uint32_t* __restrict__ hist,
+    int G, SpreadState* __restrict__ state) {
+    __shared__ uint32_t h[kSpreadBins];
+    __shared__ uint32_t wave_tot[kPlanWaves];
+    __shared__ uint32_t pick[3];
+    const int tid = threadIdx.x;
+    const int P = K - Kb;
+    const int64_t n_pool = static_cast<int64_t>(T) * P, want = B - static_cast<int64_t>(T) * Kb;
+    if (want <= 0 || want >= n_pool) return;   // nothing or everything from the pool: no search
+    uint32_t b1 = 0, b2 = 0;
+    if (PASS == 2) {
+        uint32_t r1, c;
+        spread_find_bin(hist, G, static_cast<uint32_t>(want), wave_tot, pick, b1, r1, c);
+        if (blockIdx.x == 0 && tid == 0) {
+            state->b1 = b1;
+            state->r1 = r1;
+        }
+    } else if (PASS == 3) {
+        b1 = state->b1;
+        uint32_t r2, c;
+        spread_find_bin(hist + static_cast<size_t>(G) * kSpreadBins, G, state->r1, wave_tot, pick, b2,
+                        r2, c);
+        if (blockIdx.x == 0 && tid == 0) {
+            state->b2 = b2;
+            state->r2 = r2;
+        }
+    }
+    for (int b = tid; b < kSpreadBins; b += kSpreadThreads) h[b] = 0;
+    __syncthreads();
+    const int per = (T + G - 1) / G;
+    const int t_begin = blockIdx.x * per, t_end = min(T, t_begin + per);
+    for (int t = t_begin + tid; t < t_end; t += kSpreadThreads)
+        for (int j = Kb; j < K; ++j) {
+            const uint32_t k = ordered_key(keys[static_cast<size_t>(t) * K + j]);
+            if (PASS == 1)
+                atomicAdd(&h[k >> 21], 1u);
+            else if (PASS == 2) {
+                if ((k >> 21) == b1) atomicAdd(&h[(k >> 10) & 0x7FFu], 1u);
+            } else {
+                if ((k >> 10) == ((b1 << 11) | b2)) atomicAdd(&h[k & 0x3FFu], 1u);
+            }
+        }
+    __syncthreads();
+    uint32_t* out = hist + (static_cast<size_t>(PASS - 1) * G + blockIdx.x) * kSpreadBins;
+    for (int b = tid; b < kSpreadBins; b += kSpreadThreads) out[b] = h[b];
+}
+
+// keep_count of the workgroup's 1024 tokens (SELECT; otherwise they are read) and the ballot
+// words of its 16 batches (words may be null: selection only).
+template <bool SELECT>
+__global__ __launch_bounds__(kSpreadThreads) void spread_keep_kernel(
+    const float* __restrict__ keys, const int32_t* __restrict__ topk_ids, int T, int K, int Kb,
+    int64_t B, const uint32_t* __restrict__ hist, int G, const SpreadState* __restrict__ state,
+    int32_t* __restrict__ keep_count, uint64_t* __restrict__ words) {
+    __shared__ uint32_t wave_tot[kPlanWaves];
+    __shared__ uint32_t pick[3];
+    const int tid = threadIdx.x, lane = lane_id();
+    const int t0 = blockIdx.x * kSpreadThreads, t = t0 + tid;
+    int keep = 0;
+    if (SELECT) {
+        const int P = K - Kb;
+        const int64_t n_pool = static_cast<int64_t>(T) * P, want = B - static_cast<int64_t>(T) * Kb;
+        if (want <= 0 || want >= n_pool) {
+            keep = want <= 0 ? Kb : K;
+        } else {
+            uint32_t b3, R, n_equal;
+            spread_find_bin(hist + 2 * static_cast<size_t>(G) * kSpreadBins, G, state->r2, wave_tot,
+                            pick, b3, R, n_equal);
+            const uint32_t vstar = (state->b1 << 21) | (state->b2 << 10) | b3;
+            uint32_t gt = 0, eq = 0;
+            if (t < T)
+                for (int j = Kb; j < K; ++j) {
+                    const uint32_t k = ordered_key(keys[static_cast<size_t>(t) * K + j]);
+                    gt += k > vstar ? 1u : 0u;
+                    eq += k == vstar ? 1u : 0u;
+                }
+            if (R == n_equal) {   // no tie is split: a plain threshold
+                keep = Kb + static_cast<int>(gt + eq);
+            } else {
+                // equal keys of the tokens before this workgroup's, counted here
+                uint32_t mine = 0;
+                for (int u = tid; u < t0; u += kSpreadThreads)
+                    for (int j = Kb; j < K; ++j)
+                        mine += ordered_key(keys[static_cast<size_t>(u) * K + j]) == vstar ? 1u : 0u;
+                uint32_t earlier;
+                block_scan_excl(mine, wave_tot, &earlier);
+                const uint32_t before = earlier + block_scan_excl(eq, wave_tot, nullptr);
+                // a token's equal keys sit at consecutive ranks right after its larger ones
+                const uint32_t room = before < R ? R - before : 0u;
+                keep = Kb + static_cast<int>(gt + min(eq, room));
+            }
+        }
+        if (t < T) keep_count[t] = keep;
+    } else if (t < T) {
+        keep = keep_count[t];
+    }
+    if (words == nullptr) return;
+    uint64_t mine = 0;   // bit e: this token keeps expert e
+    if (t < T) {
+        const int kt = min(K, keep);
+        int ids[kMaxK];   // all loads first, so that they are in flight together
+#pragma unroll
+        for (int j = 0; j < kMaxK; ++j) ids[j] = j < K ? topk_ids[static_cast<size_t>(t) * K + j] : 0;
+#pragma unroll
+        for (int j = 0; j < kMaxK; ++j)
+            if (j < kt) mine |= 1ull << (ids[j] & (kWave - 1));
+    }
+    const uint64_t col = wave_transpose64(mine);   // lane e: who of the batch keeps expert e
+    if (t0 + (tid / kWave) * kWave < T) words[static_cast<size_t>(t / kWave) * kWave + lane] = col;
+}
+
+__global__ __launch_bounds__(kSpreadThreads) void spread_place_kernel(
+    const int32_t* __restrict__ topk_ids, const int32_t* __restrict__ keep_count, int T, int K,
+    int E, int64_t B, const uint64_t* __restrict__ words, int32_t* __restrict__ expert_offsets,
+    int32_t* __restrict__ row_token, int32_t* __restrict__ row_rank, int32_t* __restrict__ inv_row,
+    int bm, int32_t* __restrict__ tile_info) {
+    __shared__ int32_t part_before[kPlanWaves][kWave];
+    __shared__ int32_t part_total[kPlanWaves][kWave];
+    __shared__ int32_t expert_off[kWave + 1];
+    __shared__ int32_t before[kWave];
+    __shared__ uint64_t wd[kPlanWaves][kWave];
+    __shared__ int32_t pre[kPlanWaves][kWave];
+    const int tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
+    const int n_batch = (T + kWave - 1) / kWave;
+    const int b0 = blockIdx.x * kPlanWaves;
+    {   // lane = expert; the waves split the batches
+        const int per_seg = (n_batch + kPlanWaves - 1) / kPlanWaves;
+        const int s0 = min(n_batch, wave * per_seg), s1 = min(n_batch, s0 + per_seg);
+        int tot = 0, bef = 0;
+        for (int b = s0; b < s1; ++b) {
+            const int c = __popcll(words[static_cast<size_t>(b) * kWave + lane]);
+            tot += c;
+            bef += b < b0 ? c : 0;
+        }
+        part_total[wave][lane] = tot;
+        part_before[wave][lane] = bef;
+    }
+    __syncthreads();
+    if (wave == 0) {
+        int tot = 0, bef = 0;
+        for (int w = 0; w < kPlanWaves; ++w) {
+            tot += part_total[w][lane];
+            bef += part_before[w][lane];
+        }
+        const int incl = wave_scan_incl(lane < E ? tot : 0);
+        expert_off[lane + 1] = incl;
+        if (lane == 0) expert_off[0] = 0;
+        before[lane] = bef;
+    }
+    __syncthreads();
+    if (blockIdx.x == 0) {
+        if (tid <= E) expert_offsets[tid] = min(expert_off[tid], static_cast<int32_t>(B));
+        if (tile_info != nullptr && wave == kPlanWaves - 1)
+            write_tile_map(expert_off, E, bm, tile_info, static_cast<int>(B));
+    }
+    const int b = b0 + wave;
+    if (b < n_batch) {
+        int p = before[lane];
+        for (int bb = b0; bb < b; ++bb) p += __popcll(words[static_cast<size_t>(bb) * kWave + lane]);
+        pre[wave][lane] = p;
+        wd[wave][lane] = words[static_cast<size_t>(b) * kWave + lane];
+    }
+    __syncthreads();
+    const int t = b * kWave + lane;
+    if (b >= n_batch || t >= T) return;
+    const int kt = min(K, keep_count[t]);
+    const uint64_t below = lanemask_lt();
+    int ids[kMaxK];
+#pragma unroll
+    for (int j = 0; j < kMaxK; ++j) ids[j] = j < K ? topk_ids[static_cast<size_t>(t) * K + j] : 0;
+#pragma unroll
+    for (int j = 0; j < kMaxK; ++j) {
+        if (j >= K) continue;
+        int row = -1;
+        if (j < kt) {
+            const int e = ids[j] & (kWave - 1);
+            row = expert_off[e] + pre[wave][e] + __popcll(wd[wave][e] & below);
+            if (row < B) {   // holds whenever sum_t keep_count[t] <= budget
+                row_token[row] = t;
+                row_rank[row] = j;
+            } else {
+                row = -1;
+            }
+        }
+        inv_row[static_cast<size_t>(t) * K + j] = row;
+    }
+}
+
+// the launches of the spread selection (hist: plan_spread_bytes(T) bytes of scratch)
+static void launch_spread_select(const float* keys, const int32_t* topk_ids, int T, int K, int Kb,
+                                 int64_t B, void* spread, int32_t* keep_count, uint64_t* words,
+                                 hipStream_t stream) {
+    const int G = spread_groups(T);
+    uint32_t* hist = static_cast<uint32_t*>(spread);
+    SpreadState* state = reinterpret_cast<SpreadState*>(hist + 3 * static_cast<size_t>(G) * kSpreadBins);
+    const dim3 block(kSpreadThreads);
+    hipLaunchKernelGGL(spread_hist_kernel<1>, dim3(G), block, 0, stream, keys, T, K, Kb, B, hist, G, state);
+    hipLaunchKernelGGL(spread_hist_kernel<2>, dim3(G), block, 0, stream, keys, T, K, Kb, B, hist, G, state);
+    hipLaunchKernelGGL(spread_hist_kernel<3>, dim3(G), block, 0, stream, keys, T, K, Kb, B, hist, G, state);
+    hipLaunchKernelGGL(spread_keep_kernel<true>, dim3((T + kSpreadThreads - 1) / kSpreadThreads), block,
+                       0, stream, keys, topk_ids, T, K, Kb, B, hist, G, state, keep_count, words);
+}
+
 // 0: large sizes (generic kernels), 256 / 1024: block size of the fast kernel.
 // Small problems run on 4 waves (one per SIMD): the kernel is a chain of short
 // dependent phases, and fewer waves means each instruction issues sooner.
@@ -766,7 +1037,11 @@ hipError_t launch_selector_keys(const float* topk_s, int T, int K, int mode, flo
 }
 
 hipError_t launch_select(const float* topk_s, int T, int K, int Kb, int64_t B,
-                         int32_t* keep_count, hipStream_t stream) {
+                         int32_t* keep_count, void* spread, hipStream_t stream) {
+    if (spread != nullptr && T >= kPlanSpreadTokens) {
+        launch_spread_select(topk_s, nullptr, T, K, Kb, B, spread, keep_count, nullptr, stream);
+        return hipGetLastError();
+    }
     const int nt = fast_path_threads(T, K, Kb);
     if (nt == 256)
         hipLaunchKernelGGL((plan_fast_kernel<true, false, 256>), dim3(1), dim3(256), 0, stream,
@@ -786,6 +1061,14 @@ hipError_t launch_dispatch(const int32_t* topk_ids, const int32_t* keep_count, i
                            int E, int64_t B, int32_t* expert_offsets, int32_t* row_token,
                            int32_t* row_rank, int32_t* inv_row, uint64_t* words, int32_t* prefix,
                            int bm, int32_t* tile_info, hipStream_t stream) {
+    if (T >= kPlanSpreadTokens) {
+        const dim3 grid((T + kSpreadThreads - 1) / kSpreadThreads), block(kSpreadThreads);
+        hipLaunchKernelGGL(spread_keep_kernel<false>, grid, block, 0, stream, nullptr, topk_ids, T, K,
+                           0, B, nullptr, 0, nullptr, const_cast<int32_t*>(keep_count), words);
+        hipLaunchKernelGGL(spread_place_kernel, grid, block, 0, stream, topk_ids, keep_count, T, K, E,
+                           B, words, expert_offsets, row_token, row_rank, inv_row, bm, tile_info);
+        return hipGetLastError();
+    }
     const int nt = fast_path_threads(T, K, K);
     if (nt == 256)
         hipLaunchKernelGGL((plan_fast_kernel<false, true, 256>), dim3(1), dim3(256), 0, stream,
@@ -805,7 +1088,15 @@ hipError_t launch_dispatch(const int32_t* topk_ids, const int32_t* keep_count, i
 hipError_t launch_plan(const float* topk_s, const int32_t* topk_ids, int T, int K, int Kb,
                        int64_t B, int E, int32_t* keep_count, int32_t* expert_offsets,
                        int32_t* row_token, int32_t* row_rank, int32_t* inv_row, uint64_t* words,
-                       int32_t* prefix, int bm, int32_t* tile_info, hipStream_t stream) {
+                       int32_t* prefix, int bm, int32_t* tile_info, void* spread,
+                       hipStream_t stream) {
+    if (spread != nullptr && T >= kPlanSpreadTokens) {
+        launch_spread_select(topk_s, topk_ids, T, K, Kb, B, spread, keep_count, words, stream);
+        const dim3 grid((T + kSpreadThreads - 1) / kSpreadThreads), block(kSpreadThreads);
+        hipLaunchKernelGGL(spread_place_kernel, grid, block, 0, stream, topk_ids, keep_count, T, K, E,
+                           B, words, expert_offsets, row_token, row_rank, inv_row, bm, tile_info);
+        return hipGetLastError();
+    }
     const int nt = fast_path_threads(T, K, Kb);
     if (nt == 256)
         hipLaunchKernelGGL((plan_fast_kernel<true, true, 256>), dim3(1), dim3(256), 0, stream,

@@ -12,14 +12,19 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-def gpu_route_dispatch(scores_cpu, K, Kb, budget):
+def gpu_route_dispatch(scores_cpu, K, Kb, budget, select_ws=True):
+    """select_ws: hand the selection a workspace, with which it runs on many workgroups
+    from 2048 tokens on; without, one workgroup selects whatever the size."""
     T, E = scores_cpu.shape
     desc = B.make_desc(T, 64, E, 64, K, Kb, budget, "f32")
     s = scores_cpu.to(DEV)
     ids = torch.empty((T, K), dtype=torch.int32, device=DEV)
     vals = torch.empty((T, K), dtype=torch.float32, device=DEV)
     cnt = torch.empty((T,), dtype=torch.int32, device=DEV)
-    B.allocmoe_route_from_scores(desc, s, ids, vals, cnt)
+    sel_ws = None
+    if select_ws:
+        sel_ws = torch.empty(B.allocmoe_workspace_layout(desc).scores, dtype=torch.uint8, device=DEV)
+    B.allocmoe_route_from_scores(desc, s, ids, vals, cnt, sel_ws)
     offs = torch.empty((E + 1,), dtype=torch.int32, device=DEV)
     row_token = torch.full((max(budget, 1),), -7, dtype=torch.int32, device=DEV)
     row_rank = torch.full((max(budget, 1),), -7, dtype=torch.int32, device=DEV)
@@ -67,6 +72,16 @@ def test_bit_exact_distinct_scores(T, E, K, Kb):
                     oracle_route_dispatch(scores, K, Kb, budget), (T, E, K, Kb, budget))
 
 
+@pytest.mark.parametrize("T,E,K,Kb", [(4096, 64, 6, 1), (9000, 64, 6, 0)])
+def test_bit_exact_selection_without_workspace(T, E, K, Kb):
+    # the single-workgroup selection at sizes where a workspace would spread it
+    for levels in (None, 64):
+        scores = synth.make_scores(T, E, seed=3 + T, quantize_levels=levels)
+        for budget in budgets_for(T, K, Kb):
+            assert_same(gpu_route_dispatch(scores, K, Kb, budget, select_ws=False),
+                        oracle_route_dispatch(scores, K, Kb, budget), (T, budget, levels))
+
+
 @pytest.mark.parametrize("levels", [4, 64, 1024])
 @pytest.mark.parametrize("T,E,K,Kb", [(200, 16, 4, 1), (3000, 64, 6, 1), (3000, 64, 6, 0),
                                       (2049, 60, 4, 2), (8192, 64, 6, 1), (9500, 64, 6, 1),
@@ -80,7 +95,7 @@ def test_bit_exact_with_ties(levels, T, E, K, Kb):
                     oracle_route_dispatch(scores, K, Kb, budget), (levels, T, budget))
 
 
-@pytest.mark.parametrize("T", [2500, 48])
+@pytest.mark.parametrize("T", [5000, 2500, 48])   # many workgroups, one workgroup, direct ranking
 def test_all_scores_equal(T):
     E, K = 64, 6
     scores = torch.full((T, E), 1.0 / E, dtype=torch.float32)
