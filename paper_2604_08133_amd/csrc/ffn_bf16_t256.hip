@@ -302,7 +302,12 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
     // epilogue: lane l owns token row l%32 of every row block; register quad g of
     // fragment j holds columns 32 j + 8 g + 4 (l/32) .. + 3 of the wave's columns.
     // SwiGLU: the two fragments are the W1 and W3 halves of the same 32 columns.
-    const int cq = 4 * (lane / 32);
+    // Lanes l and l + 32 hold the two halves of 8 consecutive columns of one row: quads
+    // are taken in pairs (g, g + 1) and one lane-half swap per register gives lane l the 8
+    // columns of quad g and lane l + 32 those of quad g + 1, stored as 16 bytes each (half
+    // as many store instructions and row segments as 8-byte stores; a store's cost here is
+    // the number of distinct row segments it touches).
+    const int half = lane / 32, cq = 4 * half;
     f32x4 scale[2][4];   // FP8: of the lane's columns, [fragment][quad]
     if constexpr (FP8) {
 #pragma unroll
@@ -311,13 +316,20 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
             scale[1][g] = *reinterpret_cast<const f32x4*>(sc1 + 8 * g + cq);
         }
     }
+    // w0: quad g, w1: quad g + 1 of the same fragment -> 16 bytes at column 8 (g + half)
+    auto store_pair = [&](bf16_t* at, uint2 w0, uint2 w1) {
+        const auto x = __builtin_amdgcn_permlane32_swap(w0.x, w1.x, false, false);
+        const auto y = __builtin_amdgcn_permlane32_swap(w0.y, w1.y, false, false);
+        *reinterpret_cast<uint4*>(at) = make_uint4(x[0], y[0], x[1], y[1]);
+    };
 #pragma unroll
     for (int i = 0; i < NRB; ++i) {
         const int mr = i * 32 + lane % 32;
-        if (mr >= rows) continue;
+        if (mr >= rows) continue;   // (the same for lanes l and l + 32)
         bf16_t* out = static_cast<bf16_t*>(C) + static_cast<size_t>(row0 + mr) * ldc +
-                      nt * (SWIGLU ? 128 : 256) + wave * (SWIGLU ? 32 : 64) + cq;
+                      nt * (SWIGLU ? 128 : 256) + wave * (SWIGLU ? 32 : 64) + 8 * half;
         if (SWIGLU) {
+            uint2 w[4];
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 float h[4];
@@ -331,20 +343,24 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
                     h[c] = av * bv * __builtin_amdgcn_rcpf(1.f + __expf(-av));
                 }
                 // round-to-nearest-even in the conversion unit (v_cvt_pk_bf16_f32)
-                const bf16x4 w = __builtin_convertvector(f32x4{h[0], h[1], h[2], h[3]}, bf16x4);
-                *reinterpret_cast<uint2*>(out + 8 * g) = __builtin_bit_cast(uint2, w);
+                w[g] = __builtin_bit_cast(uint2, __builtin_convertvector(f32x4{h[0], h[1], h[2], h[3]}, bf16x4));
             }
+            store_pair(out, w[0], w[1]);
+            store_pair(out + 16, w[2], w[3]);
         } else {
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < 2; ++j) {
+                uint2 w[4];
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     f32x4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2],
                                acc[i][j][4 * g + 3]};
                     if constexpr (FP8) v *= scale[j][g];
-                    const bf16x4 w = __builtin_convertvector(v, bf16x4);
-                    *reinterpret_cast<uint2*>(out + 32 * j + 8 * g) = __builtin_bit_cast(uint2, w);
+                    w[g] = __builtin_bit_cast(uint2, __builtin_convertvector(v, bf16x4));
                 }
+                store_pair(out + 32 * j, w[0], w[1]);
+                store_pair(out + 32 * j + 16, w[2], w[3]);
+            }
         }
     }
 }
