@@ -480,10 +480,17 @@ def main():
         if args.workload == "decode" and decode_cpu is not None:
             cb = cpu_baseline(w, decode_cpu, args.cpu_seconds)
         else:
-            # bounded sample for the big workloads: the same layer shapes at T = 32 tokens
-            ws_small = w.with_(T=32, budget=int(round(args.budget_ratio * 32 * w.K)))
+            # bounded sample for the big workloads: the same layer shapes (one layer) at T = 1024
+            # tokens, of which as many get their outputs computed as fit the time bound
+            Ts = min(w.T, 1024)
+            ws_small = w.with_(T=Ts, budget=int(round(args.budget_ratio * Ts * w.K)))
             cb = cpu_baseline(ws_small, synth.make_layer(ws_small, device="cpu"), args.cpu_seconds)
-            cb["sample"] = "same layer shapes at T=32 tokens: " + cb["sample"]
+            cb["sample"] = f"one layer of the same shapes at T={Ts} tokens: " + cb["sample"]
+            if nL > 1:
+                # a step of the stack is nL such layers: per-layer tokens/s divided by nL
+                cb["value_per_layer"] = cb["value"]
+                cb["value"] = cb["value"] / nL
+                cb["sample"] += f"; a step is {nL} layers: value = per-layer tokens/s / {nL}"
         out["cpu_baseline"] = cb
     print(json.dumps(out))
 
