@@ -365,6 +365,15 @@ __device__ __forceinline__ void t256_body(char* lds, const bf16_t* A, size_t lda
     }
 }
 
+// How many tiles at the end of the tile map form the light class (single tiles of at most
+// kLightRowBlocks row blocks, spread among the others and run with the deeper weight ring):
+// all of them if they are the minority, else none.  8-bit weights: none (no deeper ring for
+// them, and without it spreading the light tiles only costs).
+__device__ __forceinline__ int light_class_of(const int32_t* tile_info, bool fp8) {
+    const int tiles = tile_info[0], light = tile_info[1];
+    return (!fp8 && 2 * light <= tiles) ? light : 0;
+}
+
 template <bool SWIGLU, bool FP8>
 __global__ __launch_bounds__(kWaves* kWave, 1) void ffn_bf16_t256_kernel(StreamGroup g0,
                                                                         StreamGroup g1) {
@@ -401,7 +410,10 @@ __global__ __launch_bounds__(kWaves* kWave, 1) void ffn_bf16_t256_kernel(StreamG
         if (g0.A == nullptr) return;
         int sub = idx - S;
         if (g0.tile_info != nullptr) {
-            const int tiles = g0.tile_info[0], light = g0.tile_info[1], heavy = tiles - light;
+            // (8-bit weights: no deeper ring for the light tiles, and without it spreading
+            // them only costs: they stay at the end)
+            const int tiles = g0.tile_info[0];
+            const int light = light_class_of(g0.tile_info, FP8), heavy = tiles - light;
             // (pairs dealt in serpentine order: even rounds left to right, odd rounds
             // right to left, which evens out the XCDs' totals of the sorted tile costs)
             const int round = sub / (2 * nt0), in_pair = sub % (2 * nt0);
@@ -458,6 +470,7 @@ __global__ __launch_bounds__(kWaves* kWave, 1) void ffn_bf16_t256_kernel(StreamG
     }
     const int lane = lane_id(), wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int n_rb = (rows + 31) / 32;   // 32-row blocks that hold real rows
+    const bool deep_ring = tile_info != nullptr && only_tile && light_class_of(tile_info, FP8) > 0;
     const int KT = Kd / kStepK;
 
     // B: the two fragment streams of this wave's 64 weight columns; a stream is
@@ -479,17 +492,29 @@ __global__ __launch_bounds__(kWaves* kWave, 1) void ffn_bf16_t256_kernel(StreamG
         sc1 = SWIGLU ? sc0 + g.N : sc0 + 32;
     }
 
-#define ALLOCMOE_T256_CASE(n)                                                                       \
-    case n: {                                                                                       \
-        constexpr int kRing = (!FP8 && n <= kLightRowBlocks) ? kBRingDeep : kBRing;                 \
+    // The deeper weight ring is for light tiles that run among matrix-bound ones; where
+    // most tiles are light (few tokens) the launch as a whole is bound by the memory
+    // system, which more loads in flight per unit only crowd (measured: +3 % step time at
+    // 256 tokens, +17 % on a layer whose experts all hold 128 rows).
+#define ALLOCMOE_T256_BODY(n, ring)                                                                 \
+    do {                                                                                            \
         if (only_tile)                                                                              \
-            t256_body<SWIGLU, n, true, FP8, kRing>(lds, A, lda, row_map, b0, b1, sc0, sc1, KT,      \
-                                                   wave, lane, row0, rows, nt, g.C, ldc);           \
+            t256_body<SWIGLU, n, true, FP8, ring>(lds, A, lda, row_map, b0, b1, sc0, sc1, KT,       \
+                                                  wave, lane, row0, rows, nt, g.C, ldc);            \
         else                                                                                        \
-            t256_body<SWIGLU, n, false, FP8, kRing>(lds, A, lda, row_map, b0, b1, sc0, sc1, KT,     \
-                                                    wave, lane, row0, rows, nt, g.C, ldc);          \
-        break;                                                                                      \
-    }
+            t256_body<SWIGLU, n, false, FP8, ring>(lds, A, lda, row_map, b0, b1, sc0, sc1, KT,      \
+                                                   wave, lane, row0, rows, nt, g.C, ldc);           \
+    } while (0)
+#define ALLOCMOE_T256_CASE(n)                                                                       \
+    case n:                                                                                         \
+        if constexpr (!FP8 && n <= kLightRowBlocks) {                                               \
+            if (deep_ring) {                                                                        \
+                ALLOCMOE_T256_BODY(n, kBRingDeep);                                                  \
+                break;                                                                              \
+            }                                                                                       \
+        }                                                                                           \
+        ALLOCMOE_T256_BODY(n, kBRing);                                                              \
+        break;
     switch (n_rb) {   // uniform over the workgroup
         ALLOCMOE_T256_CASE(1)
         ALLOCMOE_T256_CASE(2)
@@ -501,6 +526,7 @@ __global__ __launch_bounds__(kWaves* kWave, 1) void ffn_bf16_t256_kernel(StreamG
         default: ALLOCMOE_T256_CASE(8)
     }
 #undef ALLOCMOE_T256_CASE
+#undef ALLOCMOE_T256_BODY
 }
 
 }  // namespace
