@@ -336,7 +336,7 @@ allocmoe_status allocmoe_dispatch(const allocmoe_layer_desc* desc, const int32_t
     ALLOCMOE_TRY(launch_dispatch(topk_ids, keep_count, desc->T, desc->K, desc->E, desc->budget,
                                  expert_offsets, row_token, row_rank, inv_row,
                                  at<uint64_t>(ws, s.words), at<int32_t>(ws, s.prefix),
-                                 kTileRowsSmall, nullptr, stream));
+                                 kTileRowsSmall, nullptr, true, stream));
     return ALLOCMOE_OK;
 }
 
@@ -567,7 +567,7 @@ allocmoe_status forward_impl(const allocmoe_layer_desc* desc, const void* X,
     ALLOCMOE_TRY(launch_plan(sel_keys, topk_ids, T, K, desc->K_base, B, E, keep_count,
                              expert_offsets, row_token, row_rank, inv_row,
                              at<uint64_t>(scr, s.words), at<int32_t>(scr, s.prefix), bm, tile_info,
-                             spread_plan ? scr + s.spread : nullptr, stream));
+                             spread_plan ? scr + s.spread : nullptr, !overlap, stream));
     if (overlap && shared_tiled) {
         for (int half = 0; half < 2; ++half) {
             ALLOCMOE_MARK_ON(half == 0 ? kEvSide0 : kEvSide1, side->stream);
@@ -680,7 +680,7 @@ allocmoe_status allocmoe_dispatch_static(const allocmoe_layer_desc* desc, const 
     ALLOCMOE_TRY(launch_dispatch(topk_ids, keep_count, desc->T, desc->K, desc->E, desc->budget,
                                  expert_offsets, row_token, row_rank, inv_row,
                                  at<uint64_t>(base, s.words), at<int32_t>(base, s.prefix),
-                                 kTileRowsSmall, nullptr, stream));
+                                 kTileRowsSmall, nullptr, true, stream));
     return ALLOCMOE_OK;
 }
 

@@ -50,6 +50,9 @@ hipError_t launch_selector_keys(const float* topk_s, int T, int K, int mode, flo
 // Every launch of the sequence costs 5-10 us whatever its size (a chain of dependent
 // memory round trips), five of them 42 us at 8192 tokens and 36 us at 4096, against 82 us
 // and 50 us for the single workgroup; at 2048 tokens both take 32 us.
+// `alone`: nothing else wants the compute units while the plan runs; below the spread
+// size the one launch then has several workgroups that repeat the selection and share
+// out the placement (beside other work extra workgroups would only queue behind it).
 constexpr int kPlanSpreadTokens = 4096;
 size_t plan_spread_bytes(int T);
 hipError_t launch_select(const float* topk_s, int T, int K, int Kb, int64_t B,
@@ -57,11 +60,11 @@ hipError_t launch_select(const float* topk_s, int T, int K, int Kb, int64_t B,
 hipError_t launch_dispatch(const int32_t* topk_ids, const int32_t* keep_count, int T, int K,
                            int E, int64_t B, int32_t* expert_offsets, int32_t* row_token,
                            int32_t* row_rank, int32_t* inv_row, uint64_t* words, int32_t* prefix,
-                           int bm, int32_t* tile_info, hipStream_t stream);
+                           int bm, int32_t* tile_info, bool alone, hipStream_t stream);
 hipError_t launch_plan(const float* topk_s, const int32_t* topk_ids, int T, int K, int Kb,
                        int64_t B, int E, int32_t* keep_count, int32_t* expert_offsets,
                        int32_t* row_token, int32_t* row_rank, int32_t* inv_row, uint64_t* words,
-                       int32_t* prefix, int bm, int32_t* tile_info, void* spread,
+                       int32_t* prefix, int bm, int32_t* tile_info, void* spread, bool alone,
                        hipStream_t stream);
 
 // ---- ffn_f32.hip : C = A B (or silu(A B1) * (A B3)) over row tiles, fp32, row-major B

@@ -19,6 +19,8 @@
 // for each batch of 64 tokens (lane = token) and each expert e the wave ballot
 // "token keeps e" is a 64-bit word M[e][batch]; the row of pair (t, e) is
 //   offset[e] + (kept pairs of e in earlier batches) + popcount(M[e][batch] below lane t).
+#include <algorithm>
+
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -390,6 +392,13 @@ __global__ __launch_bounds__(NT) void plan_fast_kernel(
     constexpr int NBINS_LOG2 = NT == 1024 ? 11 : 9;
     static_assert(NT == 1024 || NT == 256, "two block sizes");
     const int tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
+    // Launched as several workgroups (only where nothing else wants the compute units),
+    // every workgroup runs the selection and the counting phases redundantly, on its own
+    // unit and in its own LDS, with identical results and no exchange between them, and
+    // then writes its share of the placement, the one phase that is bound by the number of
+    // scattered stores a single compute unit can issue; workgroup 0 writes the rest.
+    const int n_groups = gridDim.x, group = blockIdx.x;
+    const bool writer = group == 0;
 
     // Candidate ids of this wave's batches (lane = token), all loaded up front so that
     // the loads are in flight together, and kept in registers for both uses in the
@@ -591,7 +600,8 @@ __global__ __launch_bounds__(NT) void plan_fast_kernel(
             }
         }
         __syncthreads();
-        for (int t = tid; t < T; t += NT) keep_count[t] = sh.cnt[t];
+        if (writer)
+            for (int t = tid; t < T; t += NT) keep_count[t] = sh.cnt[t];
     } else {
         for (int t = tid; t < T; t += NT) sh.cnt[t] = keep_count[t];
         __syncthreads();
@@ -652,29 +662,16 @@ __global__ __launch_bounds__(NT) void plan_fast_kernel(
             if (e == 0) sh.expert_off[0] = 0;
         }
         __syncthreads();
-        if (tid <= E) expert_offsets[tid] = min(sh.expert_off[tid], static_cast<int32_t>(B));
+        if (writer && tid <= E) expert_offsets[tid] = min(sh.expert_off[tid], static_cast<int32_t>(B));
     }
     // ---- tile map, by the last wave, beside the other waves' share of phase C (with few
     // tokens the last wave has no batch of its own)
-    if (tile_info != nullptr && wave == NW - 1)
+    if (writer && tile_info != nullptr && wave == NW - 1)
         write_tile_map(sh.expert_off, E, bm, tile_info, static_cast<int>(B));
-    // ---- C: place every pair
-#pragma unroll
-    for (int bi = 0; bi < kMaxBatches; ++bi) {
-        const int b = wave + bi * NW;
-        if (b >= n_batch) break;
-        const int t = b * kWave + lane;
-        if (t >= T) continue;
+    // ---- C: place every pair (token t = lane of batch b, candidate ids in `ids`)
+    auto place = [&](int b, int t, const int (&ids)[kMaxK]) {
         const int kt = min(K, sh.cnt[t]);
         const uint64_t below = lanemask_lt();
-        int ids[kMaxK];
-#pragma unroll
-        for (int j = 0; j < kMaxK; ++j) {
-            if (ids_held)
-                ids[j] = j < kIdsK ? held[bi][j < kIdsK ? j : 0] : 0;
-            else
-                ids[j] = j < K ? topk_ids[static_cast<size_t>(t) * K + j] : 0;
-        }
 #pragma unroll
         for (int j = 0; j < kMaxK; ++j) {
             if (j >= K) continue;
@@ -692,8 +689,37 @@ __global__ __launch_bounds__(NT) void plan_fast_kernel(
             }
             inv_row[static_cast<size_t>(t) * K + j] = row;
         }
+    };
+    if (n_groups == 1) {
+#pragma unroll
+        for (int bi = 0; bi < kMaxBatches; ++bi) {
+            const int b = wave + bi * NW;
+            if (b >= n_batch) break;
+            const int t = b * kWave + lane;
+            if (t >= T) continue;
+            int ids[kMaxK];
+#pragma unroll
+            for (int j = 0; j < kMaxK; ++j) {
+                if (ids_held)
+                    ids[j] = j < kIdsK ? held[bi][j < kIdsK ? j : 0] : 0;
+                else
+                    ids[j] = j < K ? topk_ids[static_cast<size_t>(t) * K + j] : 0;
+            }
+            place(b, t, ids);
+        }
+    } else {
+        // several workgroups: each has computed the same counts, words and prefixes and
+        // places the batches group, group + n_groups, ..., one per wave at a time
+        for (int b = group + n_groups * wave; b < n_batch; b += n_groups * NW) {
+            const int t = b * kWave + lane;
+            if (t >= T) continue;
+            int ids[kMaxK];
+#pragma unroll
+            for (int j = 0; j < kMaxK; ++j)
+                ids[j] = j < K ? topk_ids[static_cast<size_t>(t) * K + j] : 0;
+            place(b, t, ids);
+        }
     }
-
 }
 
 // ---------------------------------------------------------------------------
@@ -977,6 +1003,14 @@ inline int fast_path_threads(int T, int K, int Kb) {
     return (n_pool + kPlanThreads - 1) / kPlanThreads <= kFastMaxKeys ? kPlanThreads : 0;
 }
 
+// Workgroups of the fast kernel's launch: one beside other work (more would queue behind
+// it); alone on the chip as many as leave two 64-token batches of placement to each.
+inline int fast_path_groups(int T, bool alone) {
+    if (!alone) return 1;
+    const int n_batch = (T + kWave - 1) / kWave;
+    return std::max(1, std::min(16, n_batch / 2));
+}
+
 __global__ __launch_bounds__(kPlanThreads) void select_kernel(const float* topk_s, int T, int K,
                                                               int Kb, int64_t B,
                                                               int32_t* keep_count) {
@@ -1060,7 +1094,7 @@ hipError_t launch_select(const float* topk_s, int T, int K, int Kb, int64_t B,
 hipError_t launch_dispatch(const int32_t* topk_ids, const int32_t* keep_count, int T, int K,
                            int E, int64_t B, int32_t* expert_offsets, int32_t* row_token,
                            int32_t* row_rank, int32_t* inv_row, uint64_t* words, int32_t* prefix,
-                           int bm, int32_t* tile_info, hipStream_t stream) {
+                           int bm, int32_t* tile_info, bool alone, hipStream_t stream) {
     if (T >= kPlanSpreadTokens) {
         const dim3 grid((T + kSpreadThreads - 1) / kSpreadThreads), block(kSpreadThreads);
         hipLaunchKernelGGL(spread_keep_kernel<false>, grid, block, 0, stream, nullptr, topk_ids, T, K,
@@ -1070,12 +1104,13 @@ hipError_t launch_dispatch(const int32_t* topk_ids, const int32_t* keep_count, i
         return hipGetLastError();
     }
     const int nt = fast_path_threads(T, K, K);
+    const dim3 groups(fast_path_groups(T, alone));
     if (nt == 256)
-        hipLaunchKernelGGL((plan_fast_kernel<false, true, 256>), dim3(1), dim3(256), 0, stream,
+        hipLaunchKernelGGL((plan_fast_kernel<false, true, 256>), groups, dim3(256), 0, stream,
                            nullptr, topk_ids, T, K, 0, B, E, const_cast<int32_t*>(keep_count),
                            expert_offsets, row_token, row_rank, inv_row, bm, tile_info);
     else if (nt == 1024)
-        hipLaunchKernelGGL((plan_fast_kernel<false, true, 1024>), dim3(1), dim3(1024), 0, stream,
+        hipLaunchKernelGGL((plan_fast_kernel<false, true, 1024>), groups, dim3(1024), 0, stream,
                            nullptr, topk_ids, T, K, 0, B, E, const_cast<int32_t*>(keep_count),
                            expert_offsets, row_token, row_rank, inv_row, bm, tile_info);
     else
@@ -1088,7 +1123,7 @@ hipError_t launch_dispatch(const int32_t* topk_ids, const int32_t* keep_count, i
 hipError_t launch_plan(const float* topk_s, const int32_t* topk_ids, int T, int K, int Kb,
                        int64_t B, int E, int32_t* keep_count, int32_t* expert_offsets,
                        int32_t* row_token, int32_t* row_rank, int32_t* inv_row, uint64_t* words,
-                       int32_t* prefix, int bm, int32_t* tile_info, void* spread,
+                       int32_t* prefix, int bm, int32_t* tile_info, void* spread, bool alone,
                        hipStream_t stream) {
     if (spread != nullptr && T >= kPlanSpreadTokens) {
         launch_spread_select(topk_s, topk_ids, T, K, Kb, B, spread, keep_count, words, stream);
@@ -1098,12 +1133,13 @@ hipError_t launch_plan(const float* topk_s, const int32_t* topk_ids, int T, int 
         return hipGetLastError();
     }
     const int nt = fast_path_threads(T, K, Kb);
+    const dim3 groups(fast_path_groups(T, alone));
     if (nt == 256)
-        hipLaunchKernelGGL((plan_fast_kernel<true, true, 256>), dim3(1), dim3(256), 0, stream,
+        hipLaunchKernelGGL((plan_fast_kernel<true, true, 256>), groups, dim3(256), 0, stream,
                            topk_s, topk_ids, T, K, Kb, B, E, keep_count, expert_offsets, row_token,
                            row_rank, inv_row, bm, tile_info);
     else if (nt == 1024)
-        hipLaunchKernelGGL((plan_fast_kernel<true, true, 1024>), dim3(1), dim3(1024), 0, stream,
+        hipLaunchKernelGGL((plan_fast_kernel<true, true, 1024>), groups, dim3(1024), 0, stream,
                            topk_s, topk_ids, T, K, Kb, B, E, keep_count, expert_offsets, row_token,
                            row_rank, inv_row, bm, tile_info);
     else
