@@ -119,12 +119,24 @@ __global__ __launch_bounds__(kRouteWaves* kWave) void route_kernel(
 
 // ---------------------------------------------------------------------------
 // bf16 fast path: the gate GEMM on the matrix cores.  A workgroup of 16 waves
-// owns 16 tokens; the waves split the hidden dimension into slices of 32-wide
+// owns 16 MT tokens; the waves split the hidden dimension into slices of 32-wide
 // steps, each wave running v_mfma_f32_16x16x32_bf16 on its slice with the A
 // operand read straight from X (64 contiguous bytes per token and step) and the
 // B operand from the gate matrix re-tiled by pack_gate_kernel (one 16-byte load
 // per lane).  The partial logits meet in LDS in a fixed order, then one wave
 // per token does the softmax and the Top-K with one lane per expert.
+//
+// A workgroup is bound by the bytes that cross its compute unit's vector load path
+// (64 B per clock): the whole re-tiled gate matrix (262 KB, 327 KB with the shared
+// gate's column) plus 4 KB per token, about 6 us at 16 tokens, whatever the token
+// count.  Up to 4096 tokens that is one round of at most 256 workgroups.  Beyond,
+// MT = 2: a wave multiplies every gate fragment it loads with two 16-token
+// fragments, a workgroup owns 32 tokens and the launch stays one round up to 8192
+// tokens.  Under the 128 registers a wave of a 16-wave workgroup gets, the loads then
+// go out as two batches of two steps instead of one of four, which gives back most of
+// what the halved gate traffic saves (8192 tokens: 22.7 instead of 25 us).  The partial
+// sums of 16 waves x 2 token fragments would not fit the LDS at once: the upper eight
+// waves hand theirs to the lower eight, which add their own and publish the sums.
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 
@@ -134,37 +146,77 @@ constexpr int kRmTok = 16;
 // the hidden dimension should be one batch of loads and a wave should finish one token
 constexpr int kRmWaves = 16;
 
-template <bool GATE>
+// wave_topk_store for N tokens at once (independent chains, interleaved by the compiler)
+template <int N>
+__device__ __forceinline__ void wave_topk_store_n(const float (&score)[N], bool valid, int K,
+                                                  int32_t* const (&ids_row)[N],
+                                                  float* const (&s_row)[N], const bool (&live)[N]) {
+    const int lane = lane_id();
+    uint32_t key[N];
+    int rank[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        key[i] = valid ? ordered_key(score[i]) : 0u;
+        rank[i] = 0;
+    }
+#pragma unroll
+    for (int o = 0; o < kWave; ++o) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const uint32_t ko = __builtin_amdgcn_readlane(key[i], o);
+            rank[i] += (ko > key[i] || (ko == key[i] && o < lane)) ? 1 : 0;
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        if (live[i] && valid && rank[i] < K) {
+            ids_row[i][rank[i]] = lane;
+            s_row[i][rank[i]] = score[i];
+        }
+    }
+}
+
+template <bool GATE, int MT>
 __global__ __launch_bounds__(kRmWaves* kWave) void route_mfma_kernel(
     const bf16_t* __restrict__ X, const bf16_t* __restrict__ Gp, const float* __restrict__ bias,
     int T, int d, int E, int K, float* __restrict__ scores, int32_t* __restrict__ topk_ids,
     float* __restrict__ topk_s, float* __restrict__ sgate) {
+    static_assert(MT == 1 || MT == 2, "token fragments per wave");
     constexpr int NB = GATE ? kGateBlocks : kGateBlocks - 1;   // 16-column blocks
-    __shared__ float red[kRmWaves][NB][4][kWave];
+    constexpr int kSlots = MT == 1 ? kRmWaves : kRmWaves / 2;  // partial sums that meet in LDS
+    __shared__ float red[kSlots][MT][NB][4][kWave];
 
     const int lane = lane_id(), wave = threadIdx.x / kWave;
-    const int t0 = blockIdx.x * kRmTok;
+    const int t0 = blockIdx.x * (kRmTok * MT);
     const int KB = d / 32;
     const int per_wave = (KB + kRmWaves - 1) / kRmWaves;
     const int s0 = min(KB, wave * per_wave), s1 = min(KB, s0 + per_wave);
 
     const int m = lane % 16, kg = lane / 16;
-    const bool a_ok = t0 + m < T;
-    const bf16x8* ap =
-        reinterpret_cast<const bf16x8*>(X + static_cast<size_t>(a_ok ? t0 + m : 0) * d) + kg;
+    bool a_ok[MT];
+    const bf16x8* ap[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int t = t0 + kRmTok * mt + m;
+        a_ok[mt] = t < T;
+        ap[mt] = reinterpret_cast<const bf16x8*>(X + static_cast<size_t>(a_ok[mt] ? t : 0) * d) + kg;
+    }
     const bf16x8* bp = reinterpret_cast<const bf16x8*>(Gp) + lane;
 
-    f32x4 acc[NB];
+    f32x4 acc[MT][NB];
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) acc[mt][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
     const bf16x8 zero = {0};
-    constexpr int U = 4;
+    constexpr int U = MT == 1 ? 4 : 2;   // steps per batch of loads (registers: 16 waves, 128 each)
     int s = s0;
     for (; s + U <= s1; s += U) {
-        bf16x8 av[U], bv[U][NB];
+        bf16x8 av[U][MT], bv[U][NB];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            av[u] = a_ok ? ap[(s + u) * 4] : zero;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) av[u][mt] = a_ok[mt] ? ap[mt][(s + u) * 4] : zero;
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
                 bv[u][nb] = bp[(static_cast<size_t>(nb) * KB + s + u) * kWave];
@@ -172,46 +224,82 @@ __global__ __launch_bounds__(kRmWaves* kWave) void route_mfma_kernel(
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-                acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[u], bv[u][nb], acc[nb], 0, 0, 0);
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+                    acc[mt][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[u][mt], bv[u][nb],
+                                                                          acc[mt][nb], 0, 0, 0);
     }
     for (; s < s1; ++s) {
-        const bf16x8 av = a_ok ? ap[s * 4] : zero;
+        bf16x8 av[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) av[mt] = a_ok[mt] ? ap[mt][s * 4] : zero;
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
             const bf16x8 bv = bp[(static_cast<size_t>(nb) * KB + s) * kWave];
-            acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bv, acc[nb], 0, 0, 0);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+                acc[mt][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[mt], bv, acc[mt][nb], 0, 0, 0);
         }
     }
     // accumulator register r of lane l holds C[4*(l/16) + r][l%16]
+    if (MT == 1 || wave >= kSlots) {
+        const int slot = MT == 1 ? wave : wave - kSlots;
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
+        for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) red[wave][nb][r][lane] = acc[nb][r];
+            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) red[slot][mt][nb][r][lane] = acc[mt][nb][r];
+    }
     __syncthreads();
+    if (MT == 2) {
+        if (wave < kSlots) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        red[wave][mt][nb][r][lane] = acc[mt][nb][r] + red[wave][mt][nb][r][lane];
+        }
+        __syncthreads();
+    }
 
+    // wave w finishes token w of every token fragment
     const bool lane_is_expert = lane < E;
-    for (int q = wave; q < kRmTok; q += kRmWaves) {
-        const int t = t0 + q;
-        if (t >= T) continue;
-        const int r = q % 4, lsrc = 16 * (q / 4);
+    const int r = wave % 4, lsrc = 16 * (wave / 4);
+    float sc[MT];
+    bool live[MT];
+    int32_t* ids_row[MT];
+    float* s_row[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int t = t0 + kRmTok * mt + wave;
+        live[mt] = t < T;
+        const size_t tt = live[mt] ? t : 0;
+        ids_row[mt] = topk_ids + tt * K;
+        s_row[mt] = topk_s + tt * K;
         float logit = 0.f;
 #pragma unroll
-        for (int w = 0; w < kRmWaves; ++w) logit += red[w][lane / 16][r][lsrc + lane % 16];
+        for (int w = 0; w < kSlots; ++w) logit += red[w][mt][lane / 16][r][lsrc + lane % 16];
         if (bias != nullptr && lane_is_expert) logit += bias[lane];
         if (!lane_is_expert) logit = -INFINITY;
         const float mx = wave_max(logit);
         const float p = lane_is_expert ? expf(logit - mx) : 0.f;
         const float den = wave_sum(p);
-        const float sc = p / den;
-        if (scores != nullptr && lane_is_expert) scores[static_cast<size_t>(t) * E + lane] = sc;
-        wave_topk_store(sc, lane_is_expert, K, topk_ids + static_cast<size_t>(t) * K,
-                        topk_s + static_cast<size_t>(t) * K);
-        if (GATE && lane == 0) {
+        sc[mt] = p / den;
+        if (live[mt] && scores != nullptr && lane_is_expert) scores[tt * E + lane] = sc[mt];
+    }
+    wave_topk_store_n<MT>(sc, lane_is_expert, K, ids_row, s_row, live);
+    if (GATE && lane == 0) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            if (!live[mt]) continue;
             float g = 0.f;
 #pragma unroll
-            for (int w = 0; w < kRmWaves; ++w) g += red[w][NB - 1][r][lsrc];
-            sgate[t] = 1.f / (1.f + expf(-g));
+            for (int w = 0; w < kSlots; ++w) g += red[w][mt][NB - 1][r][lsrc];
+            sgate[t0 + kRmTok * mt + wave] = 1.f / (1.f + expf(-g));
         }
     }
 }
@@ -277,16 +365,25 @@ hipError_t launch_route_mfma(const void* X, const void* gate_packed, const float
                              bool with_gate, int T, int d, int E, int K, float* scores,
                              int32_t* topk_ids, float* topk_s, float* sgate,
                              hipStream_t stream) {
-    const dim3 grid((T + kRmTok - 1) / kRmTok);
     const bf16_t* Xb = static_cast<const bf16_t*>(X);
     const bf16_t* Gp = static_cast<const bf16_t*>(gate_packed);
     const dim3 block(kRmWaves * kWave);
-    if (with_gate)
-        hipLaunchKernelGGL(route_mfma_kernel<true>, grid, block, 0, stream, Xb, Gp, bias, T, d, E,
-                           K, scores, topk_ids, topk_s, sgate);
+    // 32 tokens per workgroup where 16 would need more workgroups than compute units
+    const bool wide = T > 256 * kRmTok;
+    const int per_group = wide ? 2 * kRmTok : kRmTok;
+    const dim3 grid((T + per_group - 1) / per_group);
+#define ALLOCMOE_ROUTE_LAUNCH(gate, mt)                                                            \
+    hipLaunchKernelGGL((route_mfma_kernel<gate, mt>), grid, block, 0, stream, Xb, Gp, bias, T, d,  \
+                       E, K, scores, topk_ids, topk_s, sgate)
+    if (with_gate && wide)
+        ALLOCMOE_ROUTE_LAUNCH(true, 2);
+    else if (with_gate)
+        ALLOCMOE_ROUTE_LAUNCH(true, 1);
+    else if (wide)
+        ALLOCMOE_ROUTE_LAUNCH(false, 2);
     else
-        hipLaunchKernelGGL(route_mfma_kernel<false>, grid, block, 0, stream, Xb, Gp, bias, T, d, E,
-                           K, scores, topk_ids, topk_s, sgate);
+        ALLOCMOE_ROUTE_LAUNCH(false, 1);
+#undef ALLOCMOE_ROUTE_LAUNCH
     return hipGetLastError();
 }
 
