@@ -13,26 +13,62 @@ namespace allocmoe {
 constexpr int kRouteTok = 4;    // tokens per workgroup
 constexpr int kRouteWaves = 4;  // waves per workgroup, splitting d
 
-// Sorted Top-K of one token's scores, lane = expert: larger score first, equal
-// scores lower expert first.  Every lane counts the lanes that precede it in
-// that order (its rank), and the lanes with rank < K store their (expert, score)
-// at position rank of the token's candidate row.
+// Largest of the 64 lanes' values, in every lane: inside a row of 16 lanes by DPP
+// permutations (lane ^ 1, lane ^ 2, mirror of 8, mirror of 16), across the rows by the
+// two row broadcasts (lane 15 of a row into the next row, lane 31 into the upper half),
+// after which lane 63 holds the result.  No LDS permutes.
+__device__ __forceinline__ uint32_t wave_max_u32_dpp(uint32_t v) {
+    constexpr int kQuad1 = 0xB1, kQuad2 = 0x4E, kRowMirror = 0x140, kRowHalfMirror = 0x141;
+    constexpr int kBcast15 = 0x142, kBcast31 = 0x143;
+    auto mx = [](uint32_t a, int b) { return max(a, static_cast<uint32_t>(b)); };
+    v = mx(v, __builtin_amdgcn_mov_dpp(static_cast<int>(v), kQuad1, 0xF, 0xF, false));
+    v = mx(v, __builtin_amdgcn_mov_dpp(static_cast<int>(v), kQuad2, 0xF, 0xF, false));
+    v = mx(v, __builtin_amdgcn_mov_dpp(static_cast<int>(v), kRowHalfMirror, 0xF, 0xF, false));
+    v = mx(v, __builtin_amdgcn_mov_dpp(static_cast<int>(v), kRowMirror, 0xF, 0xF, false));
+    // (rows the broadcast does not write keep their own value)
+    v = mx(v, __builtin_amdgcn_update_dpp(static_cast<int>(v), static_cast<int>(v), kBcast15, 0xA, 0xF, false));
+    v = mx(v, __builtin_amdgcn_update_dpp(static_cast<int>(v), static_cast<int>(v), kBcast31, 0xC, 0xF, false));
+    return static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(v), kWave - 1));
+}
+
+// Sorted Top-K of N tokens' scores at once, lane = expert: larger score first, equal
+// scores lower expert first.  K rounds of: the largest remaining key of the wave, the
+// lowest lane that holds it stores its (expert, score) at the round's position and
+// leaves.  (The N chains are independent; the compiler interleaves them.)
+template <int N>
+__device__ __forceinline__ void wave_topk_store_n(const float (&score)[N], bool valid, int K,
+                                                  int32_t* const (&ids_row)[N],
+                                                  float* const (&s_row)[N], const bool (&live)[N]) {
+    const int lane = lane_id();
+    // valid lanes: key >= 1 (scores are >= 0, so ordered_key has its top bit set)
+    uint32_t key[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) key[i] = valid ? ordered_key(score[i]) : 0u;
+    for (int k = 0; k < K; ++k) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const uint32_t top = wave_max_u32_dpp(key[i]);
+            const uint64_t holders = __ballot(key[i] == top);
+            const int winner = __builtin_ctzll(holders);   // (holders != 0: every lane takes part)
+            if (top != 0u && lane == winner) {
+                if (live[i]) {
+                    ids_row[i][k] = lane;
+                    s_row[i][k] = score[i];
+                }
+                key[i] = 0u;
+            }
+        }
+    }
+}
+
 __device__ __forceinline__ void wave_topk_store(float score, bool valid, int K,
                                                 int32_t* __restrict__ ids_row,
                                                 float* __restrict__ s_row) {
-    const int lane = lane_id();
-    // valid lanes: key >= 1 (scores are >= 0, so ordered_key has its top bit set)
-    const uint32_t key = valid ? ordered_key(score) : 0u;
-    int rank = 0;
-#pragma unroll
-    for (int o = 0; o < kWave; ++o) {
-        const uint32_t ko = __builtin_amdgcn_readlane(key, o);
-        rank += (ko > key || (ko == key && o < lane)) ? 1 : 0;
-    }
-    if (valid && rank < K) {
-        ids_row[rank] = lane;
-        s_row[rank] = score;
-    }
+    const float sc[1] = {score};
+    int32_t* const ids[1] = {ids_row};
+    float* const ss[1] = {s_row};
+    const bool live[1] = {true};
+    wave_topk_store_n<1>(sc, valid, K, ids, ss, live);
 }
 
 template <typename TIn>
@@ -145,36 +181,6 @@ constexpr int kRmTok = 16;
 // softmax, Top-K) and at most a few workgroups run per compute unit, so a wave's share of
 // the hidden dimension should be one batch of loads and a wave should finish one token
 constexpr int kRmWaves = 16;
-
-// wave_topk_store for N tokens at once (independent chains, interleaved by the compiler)
-template <int N>
-__device__ __forceinline__ void wave_topk_store_n(const float (&score)[N], bool valid, int K,
-                                                  int32_t* const (&ids_row)[N],
-                                                  float* const (&s_row)[N], const bool (&live)[N]) {
-    const int lane = lane_id();
-    uint32_t key[N];
-    int rank[N];
-#pragma unroll
-    for (int i = 0; i < N; ++i) {
-        key[i] = valid ? ordered_key(score[i]) : 0u;
-        rank[i] = 0;
-    }
-#pragma unroll
-    for (int o = 0; o < kWave; ++o) {
-#pragma unroll
-        for (int i = 0; i < N; ++i) {
-            const uint32_t ko = __builtin_amdgcn_readlane(key[i], o);
-            rank[i] += (ko > key[i] || (ko == key[i] && o < lane)) ? 1 : 0;
-        }
-    }
-#pragma unroll
-    for (int i = 0; i < N; ++i) {
-        if (live[i] && valid && rank[i] < K) {
-            ids_row[i][rank[i]] = lane;
-            s_row[i][rank[i]] = score[i];
-        }
-    }
-}
 
 template <bool GATE, int MT>
 __global__ __launch_bounds__(kRmWaves* kWave) void route_mfma_kernel(
