@@ -59,50 +59,56 @@ __device__ __forceinline__ uint64_t lane_xor(uint64_t v) {
            (static_cast<uint64_t>(lane_xor<S>(static_cast<uint32_t>(v >> 32))) << 32);
 }
 
+// Reductions over the 64 lanes (all active), result in every lane, without LDS permutes:
+// inside a row of 16 lanes by DPP permutations (lane ^ 1, lane ^ 2, mirror of 8, mirror
+// of 16: afterwards every lane holds its row's result), across the rows by the two row
+// broadcasts (lane 15 of a row into the next row, lane 31 into the upper half), after
+// which lane 63 holds the whole wave's result.  `identity` is what a lane combines with
+// where a broadcast does not reach it.  The order of the combination is fixed.
+template <typename Op>
+__device__ __forceinline__ uint32_t wave_reduce_bits(uint32_t v, uint32_t identity, Op op) {
+    constexpr int kQuad1 = 0xB1, kQuad2 = 0x4E, kRowMirror = 0x140, kRowHalfMirror = 0x141;
+    constexpr int kBcast15 = 0x142, kBcast31 = 0x143;
+#define ALLOCMOE_DPP(x, ctrl) \
+    static_cast<uint32_t>(__builtin_amdgcn_mov_dpp(static_cast<int>(x), ctrl, 0xF, 0xF, false))
+    v = op(v, ALLOCMOE_DPP(v, kQuad1));
+    v = op(v, ALLOCMOE_DPP(v, kQuad2));
+    v = op(v, ALLOCMOE_DPP(v, kRowHalfMirror));
+    v = op(v, ALLOCMOE_DPP(v, kRowMirror));
+#undef ALLOCMOE_DPP
+    v = op(v, static_cast<uint32_t>(__builtin_amdgcn_update_dpp(
+                  static_cast<int>(identity), static_cast<int>(v), kBcast15, 0xA, 0xF, false)));
+    v = op(v, static_cast<uint32_t>(__builtin_amdgcn_update_dpp(
+                  static_cast<int>(identity), static_cast<int>(v), kBcast31, 0xC, 0xF, false)));
+    return static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(v), kWave - 1));
+}
 __device__ __forceinline__ float wave_sum(float v) {
-    v += lane_xor<32>(v);
-    v += lane_xor<16>(v);
-    v += lane_xor<8>(v);
-    v += lane_xor<4>(v);
-    v += lane_xor<2>(v);
-    v += lane_xor<1>(v);
-    return v;
+    return __uint_as_float(wave_reduce_bits(__float_as_uint(v), __float_as_uint(0.f), [](uint32_t a, uint32_t b) {
+        return __float_as_uint(__uint_as_float(a) + __uint_as_float(b));
+    }));
 }
 __device__ __forceinline__ float wave_max(float v) {
-    v = fmaxf(v, lane_xor<32>(v));
-    v = fmaxf(v, lane_xor<16>(v));
-    v = fmaxf(v, lane_xor<8>(v));
-    v = fmaxf(v, lane_xor<4>(v));
-    v = fmaxf(v, lane_xor<2>(v));
-    v = fmaxf(v, lane_xor<1>(v));
-    return v;
-}
-// butterfly reductions over the 64 lanes: one exchange per power of two, largest first
-#define ALLOCMOE_BUTTERFLY(v, OP)      \
-    do {                                \
-        v = OP(v, lane_xor<32>(v));     \
-        v = OP(v, lane_xor<16>(v));     \
-        v = OP(v, lane_xor<8>(v));      \
-        v = OP(v, lane_xor<4>(v));      \
-        v = OP(v, lane_xor<2>(v));      \
-        v = OP(v, lane_xor<1>(v));      \
-    } while (0)
-__device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
-    auto mx = [](uint64_t a, uint64_t b) { return b > a ? b : a; };
-    ALLOCMOE_BUTTERFLY(v, mx);
-    return v;
+    return __uint_as_float(wave_reduce_bits(__float_as_uint(v), __float_as_uint(-INFINITY), [](uint32_t a, uint32_t b) {
+        return __float_as_uint(fmaxf(__uint_as_float(a), __uint_as_float(b)));
+    }));
 }
 __device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
-    auto mn = [](uint32_t a, uint32_t b) { return b < a ? b : a; };
-    ALLOCMOE_BUTTERFLY(v, mn);
-    return v;
+    return wave_reduce_bits(v, 0xFFFFFFFFu, [](uint32_t a, uint32_t b) { return b < a ? b : a; });
 }
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
-    auto mx = [](uint32_t a, uint32_t b) { return b > a ? b : a; };
-    ALLOCMOE_BUTTERFLY(v, mx);
+    return wave_reduce_bits(v, 0u, [](uint32_t a, uint32_t b) { return b > a ? b : a; });
+}
+// (64-bit: a butterfly, one exchange per power of two, largest first)
+__device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
+    auto mx = [](uint64_t a, uint64_t b) { return b > a ? b : a; };
+    v = mx(v, lane_xor<32>(v));
+    v = mx(v, lane_xor<16>(v));
+    v = mx(v, lane_xor<8>(v));
+    v = mx(v, lane_xor<4>(v));
+    v = mx(v, lane_xor<2>(v));
+    v = mx(v, lane_xor<1>(v));
     return v;
 }
-#undef ALLOCMOE_BUTTERFLY
 // inclusive prefix sum over the 64 lanes (all active): inside each row of 16 lanes by
 // DPP shifts that fill with zero, then the totals of the rows before (lane 15 of a row
 // broadcast to the next row, lane 31 to the upper half)

@@ -13,24 +13,6 @@ namespace allocmoe {
 constexpr int kRouteTok = 4;    // tokens per workgroup
 constexpr int kRouteWaves = 4;  // waves per workgroup, splitting d
 
-// Largest of the 64 lanes' values, in every lane: inside a row of 16 lanes by DPP
-// permutations (lane ^ 1, lane ^ 2, mirror of 8, mirror of 16), across the rows by the
-// two row broadcasts (lane 15 of a row into the next row, lane 31 into the upper half),
-// after which lane 63 holds the result.  No LDS permutes.
-__device__ __forceinline__ uint32_t wave_max_u32_dpp(uint32_t v) {
-    constexpr int kQuad1 = 0xB1, kQuad2 = 0x4E, kRowMirror = 0x140, kRowHalfMirror = 0x141;
-    constexpr int kBcast15 = 0x142, kBcast31 = 0x143;
-    auto mx = [](uint32_t a, int b) { return max(a, static_cast<uint32_t>(b)); };
-    v = mx(v, __builtin_amdgcn_mov_dpp(static_cast<int>(v), kQuad1, 0xF, 0xF, false));
-    v = mx(v, __builtin_amdgcn_mov_dpp(static_cast<int>(v), kQuad2, 0xF, 0xF, false));
-    v = mx(v, __builtin_amdgcn_mov_dpp(static_cast<int>(v), kRowHalfMirror, 0xF, 0xF, false));
-    v = mx(v, __builtin_amdgcn_mov_dpp(static_cast<int>(v), kRowMirror, 0xF, 0xF, false));
-    // (rows the broadcast does not write keep their own value)
-    v = mx(v, __builtin_amdgcn_update_dpp(static_cast<int>(v), static_cast<int>(v), kBcast15, 0xA, 0xF, false));
-    v = mx(v, __builtin_amdgcn_update_dpp(static_cast<int>(v), static_cast<int>(v), kBcast31, 0xC, 0xF, false));
-    return static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(v), kWave - 1));
-}
-
 // Sorted Top-K of N tokens' scores at once, lane = expert: larger score first, equal
 // scores lower expert first.  K rounds of: the largest remaining key of the wave, the
 // lowest lane that holds it stores its (expert, score) at the round's position and
@@ -47,7 +29,7 @@ __device__ __forceinline__ void wave_topk_store_n(const float (&score)[N], bool 
     for (int k = 0; k < K; ++k) {
 #pragma unroll
         for (int i = 0; i < N; ++i) {
-            const uint32_t top = wave_max_u32_dpp(key[i]);
+            const uint32_t top = wave_max_u32(key[i]);
             const uint64_t holders = __ballot(key[i] == top);
             const int winner = __builtin_ctzll(holders);   // (holders != 0: every lane takes part)
             if (top != 0u && lane == winner) {
