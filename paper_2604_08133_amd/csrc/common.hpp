@@ -32,6 +32,11 @@ __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
 // done by the vector unit's lane permutations (DPP) instead of a trip through the LDS
 // crossbar: l^1 and l^2 are permutations inside a quad; reversing a quad is l^3,
 // reversing 8 lanes l^7, reversing 16 lanes l^15, so l^4 = (l^7)^3 and l^8 = (l^15)^7.
+// Across rows: the row swaps of gfx950 (v_permlane16_swap exchanges the odd rows of its
+// first operand with the even rows of its second, v_permlane32_swap the upper half with
+// the lower half); given the same value twice, the first result holds rows (0,0,2,2)
+// resp. halves (lo,lo), the second rows (1,1,3,3) resp. (hi,hi), and a lane takes the
+// one that holds its partner's row.
 // All 64 lanes must be active.
 template <int S>
 __device__ __forceinline__ uint32_t lane_xor(uint32_t v) {
@@ -47,7 +52,12 @@ __device__ __forceinline__ uint32_t lane_xor(uint32_t v) {
     if (S == 8)
         return __builtin_amdgcn_mov_dpp(__builtin_amdgcn_mov_dpp(x, kRowMirror, 0xF, 0xF, false),
                                         kRowHalfMirror, 0xF, 0xF, false);
-    return static_cast<uint32_t>(__shfl_xor(x, S, kWave));
+    if (S == 16) {
+        const auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+        return (lane_id() & 16) ? r[0] : r[1];
+    }
+    const auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    return (lane_id() & 32) ? r[0] : r[1];
 }
 template <int S>
 __device__ __forceinline__ float lane_xor(float v) {
