@@ -55,7 +55,7 @@ def parse_args():
                         "baselines of Appendix A.1, at the same budget")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-sub-workloads", action="store_true",
-                   help="skip the decode / prefill / Qwen sub-records and the full-budget run")
+                   help="skip the decode / prefill / Qwen / OLMoE sub-records and the full-budget run")
     p.add_argument("--copy-probe", action="store_true",
                    help="only run a plain device copy of 1 GiB (calibrates the rocprofv3 "
                         "FETCH_SIZE / WRITE_SIZE counters)")
@@ -433,7 +433,7 @@ def main():
 
     workloads = {}
     if full_record:
-        for name in ("decode", "prefill", "qwen"):
+        for name in ("decode", "prefill", "qwen", "olmoe"):
             workloads[name] = sub_record(name, args, measured,
                                          layer_cpu=decode_cpu if name == "decode" else None)
 
